@@ -1,0 +1,159 @@
+/*
+ * cqil.h -- C ABI of the MI355X (gfx950) CQIL library.
+ *
+ * CQIL = Concurrent Computation of Quasi-Independent Layers (arxiv 2404.06709): a run of P
+ * consecutive pre-norm decoder layers is fed one shared hidden state x_G; their attention and
+ * feed-forward residual branches are summed into the next shared state (Eq.3), and attention
+ * outputs of earlier layers of the group are forwarded into the feed-forward input of later ones
+ * ("bypassing", distance d, Eq.4).  The paper places one layer per GPU (Alg.1); this library runs
+ * all P layers of a group on ONE GPU as wider kernels over weights packed once per group.
+ *
+ * General rules
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".
+ *  - All work is enqueued on the `stream` argument (a hipStream_t passed as void*; NULL = the
+ *    default stream).  No call synchronises, allocates or frees device memory: the caller owns
+ *    every buffer (packed weights, KV caches, activations, workspace).
+ *  - Return value: CQIL_OK (0) or a negative cqil_status.  Nothing aborts.  Arguments are checked
+ *    on the host before anything is launched, so a failed call has enqueued nothing
+ *    (except CQIL_EHIP, which reports a launch failure and leaves hipGetLastError() readable).
+ *  - A layer is LLaMA-1: bias-free, RMSNorm, rotary embedding with half-split pairing
+ *    (element i pairs with i + head_dim/2, angle pos * rope_base^(-2i/head_dim)), multi-head
+ *    attention with n_kv_heads == n_heads and a causal mask, SwiGLU feed-forward.  Source weight
+ *    matrices are row-major [out, in] (y = W x).
+ *  - dtype is the storage type of weights, gains, KV caches and of x_in / x_out; all sums are
+ *    accumulated in fp32.
+ *  - Thread safety: calls on different streams with disjoint workspaces and KV caches may run
+ *    concurrently; a packed group is immutable and may be shared.
+ */
+#ifndef CQIL_H
+#define CQIL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CQIL_OK = 0,
+    CQIL_EINVAL = -1, /* null pointer, non-positive size, unsupported shape or dtype */
+    CQIL_ESIZE = -2,  /* packed buffer or workspace smaller than the matching *_bytes() query */
+    CQIL_ERANGE = -3, /* max_kv_len + T exceeds max_seq, or B exceeds b_max */
+    CQIL_EHIP = -4    /* a kernel launch failed */
+} cqil_status;
+
+typedef enum { CQIL_F32 = 0, CQIL_BF16 = 1 } cqil_dtype;
+
+/* Shape of one decoder layer.  Requirements: n_heads * head_dim == d_model; head_dim even and a
+ * multiple of 8, at most 256; d_model % 8 == 0; d_ffn % 16 == 0; max_seq >= 1. */
+typedef struct {
+    int d_model, n_heads, head_dim, d_ffn, max_seq;
+    float rope_base, rms_eps;
+    int dtype; /* cqil_dtype */
+} cqil_dims;
+
+/* Source weights of one layer (Eq.2's W^Q, W^K, W^V, W^O; W_1 split into gate and up, W_2 = down). */
+typedef struct {
+    const void *wq, *wk, *wv, *wo; /* [d_model, d_model] */
+    const void *wgate, *wup;       /* [d_ffn, d_model] */
+    const void *wdown;             /* [d_model, d_ffn] */
+    const void *g_attn, *g_ffn;    /* [d_model] RMSNorm gains of the attention / feed-forward module */
+} cqil_layer;
+
+/* KV caches of one group: every layer keeps its own cache, filled from the SHARED input x_G
+ * (consequence of ATTN_l(x_G) in Eq.3).  Layout [P][b_max][n_heads][max_seq][head_dim], dtype;
+ * K is stored after the rotary embedding.  A call touches only slots kv_len[b] .. kv_len[b]+T-1
+ * of sequences b < B; every other byte is preserved bit for bit. */
+typedef struct {
+    void *k, *v;
+    int32_t *kv_len; /* [b_max] tokens already cached per sequence; the same for all P layers */
+    int b_max;
+    int max_kv_len;  /* host-side upper bound of kv_len[b] before the call: used for the range check
+                        and to size launches (kernels read exact lengths from kv_len and never write
+                        past max_seq even if this bound is wrong).  Advanced with kv_len. */
+} cqil_kv;
+
+/* Byte offsets of the parts of a packed group (all multiples of 256).
+ *   wqkv   [P][3][d_model][d_model]      rows of Wq, Wk, Wv of layer 0, then layer 1, ... (N-concat)
+ *   wo     [d_model][P][d_model]         row o = the P layers' rows o of Wo side by side (K-concat)
+ *   wgu    [P][d_ffn/16][2][16][d_model] 16 rows of Wgate, then the matching 16 rows of Wup (N-concat)
+ *   wdown  [d_model][P][d_ffn]           row o = the P layers' rows o of Wdown side by side (K-concat)
+ *   g_attn, g_ffn [P][d_model]
+ *   rope   [max_seq][head_dim/2] pairs (cos, sin) of pos * rope_base^(-2i/head_dim), fp32,
+ *          evaluated in double and rounded once
+ * With the K-concatenated layouts the sums over layers in Eq.3 / Eq.4 are part of the contraction. */
+typedef struct {
+    size_t wqkv, wo, wgu, wdown, g_attn, g_ffn, rope, total;
+} cqil_packed_layout;
+
+const char *cqil_strerror(int status);
+
+/* host-only: checks dims and P (1..16) and fills the layout; no GPU needed */
+int cqil_packed_layout_of(const cqil_dims *dims, int P, cqil_packed_layout *out /* host */);
+/* 0 if the arguments are invalid */
+size_t cqil_packed_bytes(const cqil_dims *dims, int P);
+size_t cqil_workspace_bytes(const cqil_dims *dims, int P, int B, int T);
+/* Testing aid: after cqil_group_forward has run, the workspace holds the attention outputs
+ * attn_i = ATTN_i(x) of Eq.3 / Eq.4 as fp32 [P][B*T][d_model] at this byte offset ((size_t)-1 if the
+ * arguments are invalid).  Nothing else about the workspace contents is specified. */
+size_t cqil_workspace_attn_out_offset(const cqil_dims *dims, int P, int B, int T);
+
+/* Sec.4.2 partition rule, host-only: layers s..e (1-indexed, inclusive) form consecutive groups of
+ * at most p layers, every other layer is a group of one.  group_sizes_out (host) needs room for L
+ * ints.  Example from the paper: L=32, p=2, s=9, e=30 -> 8 singles, 11 pairs, 2 singles. */
+int cqil_partition(int L, int p, int s, int e, int *group_sizes_out, int *n_groups_out);
+
+/* One-time packing of P layers into `packed` (cqil_packed_bytes() bytes, 256-byte aligned).
+ * Pure data movement for the weights (bit-exact copies at the documented indices) plus the rotary
+ * table.  layers: host array of P structs holding device pointers. */
+int cqil_pack_group(const cqil_dims *dims, int P, const cqil_layer *layers /* host */, void *packed,
+                    size_t packed_bytes, void *stream);
+
+/* One group step (Eq.4; Eq.3 when bypass_d == 0; Eq.1 when P == 1):
+ *   attn_i = ATTN_i(x)                                   i = 0..P-1, all from the same x
+ *   h_i    = x + attn_i + sum_{j : 1 <= i-j <= d} attn_j
+ *   x_out  = x + sum_i attn_i + sum_i FFN_i(h_i)
+ * x_in, x_out: [B][T][d_model] dtype; x_out may alias x_in.  T == 1 is a decode step, T > 1 a
+ * prefill chunk at positions kv_len[b] .. kv_len[b]+T-1 (causal over cache + new tokens).
+ * bypass_d < 0 is CQIL_EINVAL; bypass_d >= P acts as P-1.  advance_kv_len != 0 adds T to
+ * kv_len[b] (b < B) and to kv->max_kv_len after the step. workspace: cqil_workspace_bytes()
+ * bytes, 256-byte aligned, contents undefined on entry and exit. */
+int cqil_group_forward(const cqil_dims *dims, int P, int bypass_d, const void *packed, cqil_kv *kv /* host */,
+                       const void *x_in, void *x_out, int B, int T, int advance_kv_len, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/* Whole model (Alg.1 around LLaMA's embedding, final RMSNorm and lm head). */
+typedef struct {
+    cqil_dims dims;
+    int vocab;
+    int n_groups;
+    const int *group_sizes;     /* host [n_groups], from cqil_partition */
+    const void *const *packed;  /* host [n_groups] of device pointers, one packed group each */
+    void *const *k_cache;       /* host [n_groups] of device pointers, [P_g][b_max][n][max_seq][head_dim] */
+    void *const *v_cache;       /* host [n_groups] */
+    int32_t *kv_len;            /* device [b_max], shared by all layers */
+    int b_max;
+    int max_kv_len;             /* host-side bound, see cqil_kv */
+    const void *embedding;      /* [vocab][d_model] dtype */
+    const void *g_final;        /* [d_model] */
+    const void *lm_head;        /* [vocab][d_model] */
+} cqil_model;
+
+size_t cqil_model_workspace_bytes(const cqil_model *m /* host */, int B, int T);
+
+/* tokens [B][T] int32 -> groups in order -> final norm of the last position -> logits -> greedy token
+ * (lowest index among equal maxima).  hidden_out (optional) [B][T][d_model] dtype is the state after
+ * the last layer; logits_out (optional) [B][vocab] fp32; next_token_out (optional) [B] int32.
+ * kv_len and m->max_kv_len advance by T when advance_kv_len != 0. */
+int cqil_model_forward(cqil_model *m /* host */, const int32_t *tokens, int B, int T, int bypass_d,
+                       int advance_kv_len, void *hidden_out, float *logits_out, int32_t *next_token_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Library build information (host-only). */
+const char *cqil_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CQIL_H */

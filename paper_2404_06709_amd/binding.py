@@ -1,0 +1,208 @@
+"""Thin ctypes binding of libcqil.so: argument marshalling only.
+
+Function names follow the C ABI in ``include/cqil.h``.  torch tensors supply device memory
+(``data_ptr()``) and the current HIP stream; every step of the path runs inside the library.
+There is no fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcqil.so")
+
+CQIL_F32, CQIL_BF16 = 0, 1
+CQIL_OK, CQIL_EINVAL, CQIL_ESIZE, CQIL_ERANGE, CQIL_EHIP = 0, -1, -2, -3, -4
+
+
+class cqil_dims(C.Structure):
+    _fields_ = [("d_model", C.c_int), ("n_heads", C.c_int), ("head_dim", C.c_int), ("d_ffn", C.c_int),
+                ("max_seq", C.c_int), ("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int)]
+
+
+class cqil_layer(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "g_attn", "g_ffn")]
+
+
+class cqil_kv(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("kv_len", C.c_void_p), ("b_max", C.c_int),
+                ("max_kv_len", C.c_int)]
+
+
+class cqil_packed_layout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in
+                ("wqkv", "wo", "wgu", "wdown", "g_attn", "g_ffn", "rope", "total")]
+
+
+class cqil_model(C.Structure):
+    _fields_ = [("dims", cqil_dims), ("vocab", C.c_int), ("n_groups", C.c_int),
+                ("group_sizes", C.POINTER(C.c_int)), ("packed", C.POINTER(C.c_void_p)),
+                ("k_cache", C.POINTER(C.c_void_p)), ("v_cache", C.POINTER(C.c_void_p)),
+                ("kv_len", C.c_void_p), ("b_max", C.c_int), ("max_kv_len", C.c_int),
+                ("embedding", C.c_void_p), ("g_final", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+class CqilError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libcqil.so; raises if it has not been built (there is no other implementation)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2404_06709_amd.build` first")
+        L = C.CDLL(LIB_PATH)
+        L.cqil_version.restype = C.c_char_p
+        L.cqil_strerror.restype = C.c_char_p
+        L.cqil_strerror.argtypes = [C.c_int]
+        L.cqil_packed_layout_of.argtypes = [C.POINTER(cqil_dims), C.c_int, C.POINTER(cqil_packed_layout)]
+        L.cqil_packed_bytes.restype = C.c_size_t
+        L.cqil_packed_bytes.argtypes = [C.POINTER(cqil_dims), C.c_int]
+        L.cqil_workspace_bytes.restype = C.c_size_t
+        L.cqil_workspace_bytes.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_int]
+        L.cqil_workspace_attn_out_offset.restype = C.c_size_t
+        L.cqil_workspace_attn_out_offset.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_int]
+        L.cqil_partition.argtypes = [C.c_int] * 4 + [C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.cqil_pack_group.argtypes = [C.POINTER(cqil_dims), C.c_int, C.POINTER(cqil_layer), C.c_void_p, C.c_size_t,
+                                      C.c_void_p]
+        L.cqil_group_forward.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_void_p, C.POINTER(cqil_kv),
+                                         C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
+                                         C.c_void_p]
+        L.cqil_model_workspace_bytes.restype = C.c_size_t
+        L.cqil_model_workspace_bytes.argtypes = [C.POINTER(cqil_model), C.c_int, C.c_int]
+        L.cqil_model_forward.argtypes = [C.POINTER(cqil_model), C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().cqil_strerror(int(status)).decode()
+
+
+def version() -> str:
+    return lib().cqil_version().decode()
+
+
+def dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return CQIL_F32
+    if dt == torch.bfloat16:
+        return CQIL_BF16
+    raise TypeError(f"unsupported dtype {dt}")
+
+
+def make_dims(d_model: int, n_heads: int, head_dim: int, d_ffn: int, max_seq: int, dtype: torch.dtype,
+              rope_base: float = 10000.0, rms_eps: float = 1e-6) -> cqil_dims:
+    return cqil_dims(d_model, n_heads, head_dim, d_ffn, max_seq, rope_base, rms_eps, dtype_code(dtype))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def cqil_packed_layout_of(dims: cqil_dims, P: int) -> cqil_packed_layout:
+    out = cqil_packed_layout()
+    rc = lib().cqil_packed_layout_of(C.byref(dims), P, C.byref(out))
+    if rc:
+        raise CqilError(rc, "cqil_packed_layout_of")
+    return out
+
+
+def cqil_packed_bytes(dims: cqil_dims, P: int) -> int:
+    return int(lib().cqil_packed_bytes(C.byref(dims), P))
+
+
+def cqil_workspace_bytes(dims: cqil_dims, P: int, B: int, T: int) -> int:
+    return int(lib().cqil_workspace_bytes(C.byref(dims), P, B, T))
+
+
+def cqil_workspace_attn_out_offset(dims: cqil_dims, P: int, B: int, T: int) -> int:
+    return int(lib().cqil_workspace_attn_out_offset(C.byref(dims), P, B, T))
+
+
+def cqil_partition(L: int, p: int, s: int, e: int) -> List[int]:
+    sizes = (C.c_int * max(L, 1))()
+    n = C.c_int(0)
+    rc = lib().cqil_partition(L, p, s, e, sizes, C.byref(n))
+    if rc:
+        raise CqilError(rc, "cqil_partition")
+    return [int(sizes[i]) for i in range(n.value)]
+
+
+def layer_struct(layer: Dict[str, torch.Tensor]) -> cqil_layer:
+    return cqil_layer(*[layer[k].data_ptr() for k in
+                        ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "g_attn", "g_ffn")])
+
+
+def cqil_pack_group(dims: cqil_dims, layers: Sequence[Dict[str, torch.Tensor]], packed: torch.Tensor) -> None:
+    """layers: P dicts of contiguous device tensors; packed: uint8 device tensor of cqil_packed_bytes()."""
+    P = len(layers)
+    arr = (cqil_layer * P)(*[layer_struct(L) for L in layers])
+    rc = lib().cqil_pack_group(C.byref(dims), P, arr, _ptr(packed), packed.numel() * packed.element_size(), _stream())
+    if rc:
+        raise CqilError(rc, "cqil_pack_group")
+
+
+def make_kv(k: torch.Tensor, v: torch.Tensor, kv_len: torch.Tensor, max_kv_len: int) -> cqil_kv:
+    """k, v: [P, b_max, n_heads, max_seq, head_dim]; kv_len: int32 [b_max] on the device."""
+    assert kv_len.dtype == torch.int32
+    return cqil_kv(k.data_ptr(), v.data_ptr(), kv_len.data_ptr(), k.shape[1], int(max_kv_len))
+
+
+def cqil_group_forward(dims: cqil_dims, P: int, bypass_d: int, packed: torch.Tensor, kv: cqil_kv,
+                       x_in: torch.Tensor, x_out: torch.Tensor, B: int, T: int, advance_kv_len: bool,
+                       workspace: torch.Tensor) -> None:
+    rc = lib().cqil_group_forward(C.byref(dims), P, bypass_d, _ptr(packed), C.byref(kv), _ptr(x_in), _ptr(x_out), B, T,
+                                  1 if advance_kv_len else 0, _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream())
+    if rc:
+        raise CqilError(rc, "cqil_group_forward")
+
+
+class Model:
+    """Owns the host-side arrays a cqil_model points to (and keeps the tensors alive)."""
+
+    def __init__(self, dims: cqil_dims, group_sizes: Sequence[int], packed: Sequence[torch.Tensor],
+                 k_cache: Sequence[torch.Tensor], v_cache: Sequence[torch.Tensor], kv_len: torch.Tensor,
+                 embedding: torch.Tensor, g_final: torch.Tensor, lm_head: torch.Tensor, max_kv_len: int = 0):
+        n = len(group_sizes)
+        assert len(packed) == n and len(k_cache) == n and len(v_cache) == n
+        self._keep = (list(packed), list(k_cache), list(v_cache), kv_len, embedding, g_final, lm_head)
+        self._gs = (C.c_int * n)(*[int(g) for g in group_sizes])
+        self._pk = (C.c_void_p * n)(*[t.data_ptr() for t in packed])
+        self._kc = (C.c_void_p * n)(*[t.data_ptr() for t in k_cache])
+        self._vc = (C.c_void_p * n)(*[t.data_ptr() for t in v_cache])
+        self.c = cqil_model(dims, lm_head.shape[0], n, self._gs, self._pk, self._kc, self._vc, kv_len.data_ptr(),
+                            k_cache[0].shape[1], int(max_kv_len), embedding.data_ptr(), g_final.data_ptr(),
+                            lm_head.data_ptr())
+
+
+def cqil_model_workspace_bytes(model: Model, B: int, T: int) -> int:
+    return int(lib().cqil_model_workspace_bytes(C.byref(model.c), B, T))
+
+
+def cqil_model_forward(model: Model, tokens: torch.Tensor, B: int, T: int, bypass_d: int, advance_kv_len: bool,
+                       hidden_out: Optional[torch.Tensor], logits_out: Optional[torch.Tensor],
+                       next_token_out: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    assert tokens.dtype == torch.int32
+    rc = lib().cqil_model_forward(C.byref(model.c), _ptr(tokens), B, T, bypass_d, 1 if advance_kv_len else 0,
+                                  _ptr(hidden_out), _ptr(logits_out), _ptr(next_token_out), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream())
+    if rc:
+        raise CqilError(rc, "cqil_model_forward")

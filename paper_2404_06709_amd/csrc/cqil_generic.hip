@@ -1,0 +1,451 @@
+// Token-parallel group step for any batch B and any number of new tokens T (M = B*T token rows), plus the
+// model-level kernels (embedding gather, final norm + lm head, greedy argmax).
+//
+// Steps (same order as the decode path, unfused):
+//   rmsnorm_multi   one statistic per token, P gains                          -> nrm [P][M][d_model]
+//   gemm (QKV)      grouped over layers                                       -> qkv [M][P*3*d_model]
+//   rope_append     rotary embedding of q (in place) and k, KV append
+//   attention       causal over cache + new tokens, online softmax            -> ctx [P][M][d_model]
+//   gemm (O)        grouped over layers, fp32 output                          -> a   [P][M][d_model]
+//   bypass_norm     h_i = x + a_i + window (Eq.4), FFN norms, x + sum a_i      -> nrm, resid
+//   gemm (gate/up)  grouped over layers                                       -> gu  [M][P*2*d_ffn]
+//   swiglu                                                                    -> u   [M][P*d_ffn]
+//   gemm (down)     one contraction over the K-concatenated Wdown + resid     -> x_out
+#include "cqil_dev.h"
+#include "cqil_gemv.h"
+#include "cqil_internal.h"
+
+namespace cqil {
+
+// ------------------------------------------------------------------------------------------ elementwise
+// nrm[l][m][k] = x[m][k] * rsqrt(mean x[m]^2 + eps) * g[l][k]; one workgroup per token row
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_multi_kernel(const T* __restrict__ x, const T* __restrict__ g,
+                                                            T* __restrict__ nrm, int P, int M, int d_model, float eps) {
+    __shared__ float scratch[16];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const T* xr = x + (size_t)m * d_model;
+    float ss = 0.f;
+    for (int k = tid; k < d_model; k += 256) {
+        const float v = elem<T>::load(xr + k);
+        ss += v * v;
+    }
+    ss = block_sum(ss, scratch);
+    const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
+    for (int l = 0; l < P; ++l) {
+        T* out = nrm + ((size_t)l * M + m) * d_model;
+        const T* gl = g + (size_t)l * d_model;
+        for (int k = tid; k < d_model; k += 256) elem<T>::store(out + k, elem<T>::load(xr + k) * r * elem<T>::load(gl + k));
+    }
+}
+
+// Rotary embedding and KV append for every (token, layer, head).  grid = (M, P*n_heads), block = head_dim/2.
+template <typename T>
+__global__ void rope_append_kernel(T* __restrict__ qkv, const float2* __restrict__ rope,
+                                   const int32_t* __restrict__ kv_len, T* __restrict__ kc, T* __restrict__ vc, int P,
+                                   int T_new, int n_heads, int d_k, int max_seq, int b_max) {
+    const int m = blockIdx.x, b = m / T_new, t = m % T_new;
+    const int lh = blockIdx.y, l = lh / n_heads, h = lh % n_heads;
+    const int half = d_k >> 1, i = threadIdx.x;
+    const int pos = kv_len[b] + t;
+    if (i >= half || pos < 0 || pos >= max_seq) return;
+    const size_t d_model = (size_t)n_heads * d_k;
+    T* row = qkv + (size_t)m * P * 3 * d_model + (size_t)l * 3 * d_model + (size_t)h * d_k;
+    const float2 cs = rope[(size_t)pos * half + i];
+    const size_t slot = ((((size_t)l * b_max + b) * n_heads + h) * max_seq + pos) * d_k;
+    {
+        const float a = elem<T>::load(row + i), c = elem<T>::load(row + i + half);
+        elem<T>::store(row + i, a * cs.x - c * cs.y);
+        elem<T>::store(row + i + half, c * cs.x + a * cs.y);
+    }
+    {
+        const T* kr = row + d_model;
+        const float a = elem<T>::load(kr + i), c = elem<T>::load(kr + i + half);
+        elem<T>::store(kc + slot + i, a * cs.x - c * cs.y);
+        elem<T>::store(kc + slot + i + half, c * cs.x + a * cs.y);
+    }
+    {
+        const T* vr = row + 2 * d_model;
+        vc[slot + i] = vr[i];
+        vc[slot + i + half] = vr[i + half];
+    }
+}
+
+// Attention of one query (token m, layer l, head h) over slots 0 .. kv_len[b]+t, online softmax.
+// grid = (M, P*n_heads), 256 threads; LPS lanes share one cache slot.
+template <typename T, int LPS>
+__global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__ qkv, const T* __restrict__ kc,
+                                                            const T* __restrict__ vc,
+                                                            const int32_t* __restrict__ kv_len, T* __restrict__ ctx,
+                                                            int P, int M, int T_new, int n_heads, int max_seq,
+                                                            int b_max) {
+    constexpr int V = elem<T>::kVec;
+    constexpr int DK = LPS * V;
+    constexpr int SPW = kWave / LPS;
+    __shared__ float red_m[4], red_l[4];
+    __shared__ float accs[4][DK];
+    const int m = blockIdx.x, b = m / T_new, t = m % T_new;
+    const int lh = blockIdx.y, l = lh / n_heads, h = lh % n_heads;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int sub = lane % LPS, sg = lane / LPS;
+    int S = kv_len[b] + t + 1;
+    if (S > max_seq) S = max_seq;
+    const size_t d_model = (size_t)n_heads * DK;
+    T* out = ctx + ((size_t)l * M + m) * d_model + (size_t)h * DK;
+    if (S < 1) return;
+    const float scale = 1.0f / sqrtf((float)DK);
+    float qv[V];
+    {
+        float f[V];
+        elem<T>::unpack(load16(qkv + (size_t)m * P * 3 * d_model + (size_t)l * 3 * d_model + (size_t)h * DK + sub * V), f);
+#pragma unroll
+        for (int j = 0; j < V; ++j) qv[j] = f[j] * scale;
+    }
+    const size_t head_off = (((size_t)l * b_max + b) * n_heads + h) * (size_t)max_seq * DK;
+    const T* kb = kc + head_off;
+    const T* vb = vc + head_off;
+    float mx = -INFINITY, lsum = 0.f, acc[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] = 0.f;
+    for (int s = w * SPW + sg; s < S; s += 4 * SPW) {
+        // the LPS lanes of a slot group run this loop together (s depends on lane only through sg)
+        float f[V], dot = 0.f;
+        elem<T>::unpack(load16(kb + (size_t)s * DK + sub * V), f);
+#pragma unroll
+        for (int j = 0; j < V; ++j) dot = fmaf(f[j], qv[j], dot);
+#pragma unroll
+        for (int off = LPS / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, kWave);
+        const float nm = fmaxf(mx, dot);
+        const float corr = expf(mx - nm), p = expf(dot - nm);   // exp(-inf) = 0 on the first slot
+        elem<T>::unpack(load16(vb + (size_t)s * DK + sub * V), f);
+        lsum = lsum * corr + p;
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = fmaf(p, f[j], acc[j] * corr);
+        mx = nm;
+    }
+    // merge the slot groups of the wave, then the waves
+    float wm = mx;
+#pragma unroll
+    for (int off = LPS; off < kWave; off <<= 1) wm = fmaxf(wm, __shfl_xor(wm, off, kWave));
+    const float sc = (mx == -INFINITY) ? 0.f : expf(mx - wm);
+    lsum *= sc;
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] *= sc;
+#pragma unroll
+    for (int off = LPS; off < kWave; off <<= 1) {
+        lsum += __shfl_xor(lsum, off, kWave);
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] += __shfl_xor(acc[j], off, kWave);
+    }
+    if (lane == 0) { red_m[w] = wm; red_l[w] = lsum; }
+    if (sg == 0) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) accs[w][sub * V + j] = acc[j];
+    }
+    __syncthreads();
+    if (tid < DK) {
+        float gm = red_m[0];
+        for (int i = 1; i < 4; ++i) gm = fmaxf(gm, red_m[i]);
+        float L = 0.f, c = 0.f;
+        for (int i = 0; i < 4; ++i) {
+            const float e = (red_m[i] == -INFINITY) ? 0.f : expf(red_m[i] - gm);
+            L += e * red_l[i];
+            c += e * accs[i][tid];
+        }
+        elem<T>::store(out + tid, c / L);
+    }
+}
+
+// Bypass window, FFN norms and the residual carrier for one token row per workgroup:
+//   h_i = x + sum_{j=max(0,i-d)}^{i} a_j ; nrm_i = RMSNorm(h_i) g_i ; resid = x + sum_j a_j
+template <typename T>
+__global__ __launch_bounds__(256) void bypass_norm_kernel(const T* __restrict__ x, const float* __restrict__ a,
+                                                          const T* __restrict__ g_ffn, T* __restrict__ nrm,
+                                                          float* __restrict__ resid, int P, int bypass_d, int M,
+                                                          int d_model, float eps) {
+    __shared__ float scratch[16];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const T* xr = x + (size_t)m * d_model;
+    for (int i = 0; i < P; ++i) {
+        const int jlo = max(0, i - bypass_d);
+        float ss = 0.f;
+        for (int k = tid; k < d_model; k += 256) {
+            float hv = elem<T>::load(xr + k);
+            for (int j = jlo; j <= i; ++j) hv += a[((size_t)j * M + m) * d_model + k];
+            ss += hv * hv;
+        }
+        ss = block_sum(ss, scratch);
+        const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
+        const T* gi = g_ffn + (size_t)i * d_model;
+        T* out = nrm + ((size_t)i * M + m) * d_model;
+        for (int k = tid; k < d_model; k += 256) {
+            float hv = elem<T>::load(xr + k);
+            for (int j = jlo; j <= i; ++j) hv += a[((size_t)j * M + m) * d_model + k];
+            elem<T>::store(out + k, hv * r * elem<T>::load(gi + k));
+        }
+    }
+    for (int k = tid; k < d_model; k += 256) {
+        float v = elem<T>::load(xr + k);
+        for (int j = 0; j < P; ++j) v += a[((size_t)j * M + m) * d_model + k];
+        resid[(size_t)m * d_model + k] = v;
+    }
+}
+
+// u[m][l*f + j] = silu(gate) * up, reading the block-interleaved gate/up columns
+template <typename T>
+__global__ void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ u, int P, int M, int d_ffn) {
+    const size_t total = (size_t)M * P * d_ffn;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t m = i / ((size_t)P * d_ffn);
+        const int lj = (int)(i % ((size_t)P * d_ffn));
+        const int l = lj / d_ffn, j = lj % d_ffn;
+        const T* row = gu + m * (size_t)P * 2 * d_ffn + (size_t)l * 2 * d_ffn + (size_t)(j / kGuBlock) * 2 * kGuBlock + j % kGuBlock;
+        const float g = elem<T>::load(row), up = elem<T>::load(row + kGuBlock);
+        elem<T>::store(u + i, g / (1.0f + expf(-g)) * up);
+    }
+}
+
+// ------------------------------------------------------------------------------------------ plain GEMM
+// C[m][n] = sum_k A[m][k] * B[n][k]  (+ R[m][n]), fp32 accumulate, 64x64 tile, 16-wide K steps, 4x4 per thread.
+// blockIdx.z selects a group: pointers advance by the given element strides.  K % 4 == 0.
+template <typename AT, typename BT, typename CT, bool ADD_R>
+__global__ __launch_bounds__(256) void gemm_nt_kernel(const AT* __restrict__ A, const BT* __restrict__ B,
+                                                      CT* __restrict__ C, const float* __restrict__ R, int M, int N,
+                                                      int K, size_t lda, size_t ldb, size_t ldc, size_t sA, size_t sB,
+                                                      size_t sC) {
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float As[BK][BM + 4];
+    __shared__ float Bs[BK][BN + 4];
+    A += (size_t)blockIdx.z * sA; B += (size_t)blockIdx.z * sB; C += (size_t)blockIdx.z * sC;
+    const int tid = threadIdx.x;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int tx = tid % 16, ty = tid / 16;
+    const int lr = tid / 4, lc = (tid % 4) * 4;  // loader: row lr of the tile, 4 consecutive k
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        {
+            const int gm = m0 + lr, gk = k0 + lc;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (gm < M && gk < K)
+                for (int j = 0; j < 4; ++j) v[j] = elem<AT>::load(A + (size_t)gm * lda + gk + j);
+            for (int j = 0; j < 4; ++j) As[lc + j][lr] = v[j];
+        }
+        {
+            const int gn = n0 + lr, gk = k0 + lc;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (gn < N && gk < K)
+                for (int j = 0; j < 4; ++j) v[j] = elem<BT>::load(B + (size_t)gn * ldb + gk + j);
+            for (int j = 0; j < 4; ++j) Bs[lc + j][lr] = v[j];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 4; ++i) {
+        const int gm = m0 + ty * 4 + i;
+        if (gm >= M) continue;
+        for (int j = 0; j < 4; ++j) {
+            const int gn = n0 + tx * 4 + j;
+            if (gn >= N) continue;
+            float v = acc[i][j];
+            if (ADD_R) v += R[(size_t)gm * N + gn];
+            elem<CT>::store(C + (size_t)gm * ldc + gn, v);
+        }
+    }
+}
+
+template <typename AT, typename BT, typename CT, bool ADD_R>
+static void gemm_nt(const AT* A, const BT* B, CT* C, const float* R, int M, int N, int K, size_t lda, size_t ldb,
+                    size_t ldc, int groups, size_t sA, size_t sB, size_t sC, hipStream_t st) {
+    dim3 grid((N + 63) / 64, (M + 63) / 64, groups);
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_nt_kernel<AT, BT, CT, ADD_R>), grid, dim3(256), 0, st, A, B, C, R, M, N, K,
+                       lda, ldb, ldc, sA, sB, sC);
+}
+
+__global__ void advance_kernel(int32_t* kv_len, int B, int T) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) kv_len[b] += T;
+}
+
+hipError_t launch_advance(int32_t* kv_len, int B, int T, hipStream_t st) {
+    hipLaunchKernelGGL(advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, kv_len, B, T);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
+    const cqil_dims& d = s.d;
+    const int P = s.P, dm = d.d_model, f = d.d_ffn, dk = d.head_dim, nh = d.n_heads;
+    const int M = s.B * s.T;
+    const T* wqkv = (const T*)(s.packed + s.pl.wqkv);
+    const T* wo = (const T*)(s.packed + s.pl.wo);
+    const T* wgu = (const T*)(s.packed + s.pl.wgu);
+    const T* wdown = (const T*)(s.packed + s.pl.wdown);
+    const T* g_attn = (const T*)(s.packed + s.pl.g_attn);
+    const T* g_ffn = (const T*)(s.packed + s.pl.g_ffn);
+    const float2* rope = (const float2*)(s.packed + s.pl.rope);
+    T* nrm = (T*)(s.ws + s.wl.nrm);
+    T* qkv = (T*)(s.ws + s.wl.qkv);
+    T* ctx = (T*)(s.ws + s.wl.ctx_act);
+    float* a = (float*)(s.ws + s.wl.a);
+    float* resid = (float*)(s.ws + s.wl.resid);
+    T* gu = (T*)(s.ws + s.wl.gu);
+    T* u = (T*)(s.ws + s.wl.u_act);
+    const T* x = (const T*)s.x_in;
+    const int bd = s.bypass_d >= P ? P - 1 : s.bypass_d;
+    const size_t Mdm = (size_t)M * dm;
+
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(rmsnorm_multi_kernel<T>), dim3(M), dim3(256), 0, st, x, g_attn, nrm, P, M, dm,
+                       d.rms_eps);
+    gemm_nt<T, T, T, false>(nrm, wqkv, qkv, nullptr, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm,
+                            (size_t)3 * dm * dm, (size_t)3 * dm, st);
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M, P * nh), dim3(((dk / 2) + 63) / 64 * 64), 0, st,
+                       qkv, rope, s.kv_len, (T*)s.kc, (T*)s.vc, P, s.T, nh, dk, d.max_seq, s.b_max);
+    const int lps = dk * (int)sizeof(T) / 16;
+#define CQIL_ATTN(LPS)                                                                                               \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_generic_kernel<T, LPS>), dim3(M, P * nh), dim3(256), 0, st, (const T*)qkv, \
+                       (const T*)s.kc, (const T*)s.vc, s.kv_len, ctx, P, M, s.T, nh, d.max_seq, s.b_max)
+    switch (lps) {
+        case 4: CQIL_ATTN(4); break;
+        case 8: CQIL_ATTN(8); break;
+        case 16: CQIL_ATTN(16); break;
+        case 32: CQIL_ATTN(32); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef CQIL_ATTN
+    gemm_nt<T, T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, (size_t)dm, Mdm, st);
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(256), 0, st, x, a, g_ffn, nrm, resid, P, bd,
+                       M, dm, d.rms_eps);
+    gemm_nt<T, T, T, false>(nrm, wgu, gu, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * 2 * f, P, Mdm, (size_t)2 * f * dm,
+                            (size_t)2 * f, st);
+    {
+        const size_t total = (size_t)M * P * f;
+        size_t g = (total + 255) / 256;
+        if (g > 65536) g = 65536;
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(swiglu_kernel<T>), dim3((int)g), dim3(256), 0, st, (const T*)gu, u, P, M, f);
+    }
+    gemm_nt<T, T, T, true>(u, wdown, (T*)s.x_out, resid, M, dm, P * f, (size_t)P * f, (size_t)P * f, dm, 1, 0, 0, 0, st);
+    if (s.advance) hipLaunchKernelGGL(advance_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st, s.kv_len, s.B, s.T);
+    return hipGetLastError();
+}
+
+hipError_t launch_generic_step(const StepArgs& s, hipStream_t st) {
+    return s.d.dtype == CQIL_BF16 ? generic_step_t<bf16_t>(s, st) : generic_step_t<float>(s, st);
+}
+
+// ------------------------------------------------------------------------------------------ model level
+template <typename T>
+__global__ void embedding_kernel(const T* __restrict__ emb, const int32_t* __restrict__ tokens, T* __restrict__ x,
+                                 int M, int vocab, int vec_per_row) {
+    const int m = blockIdx.x;
+    int tok = tokens[m];
+    tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);  // never read outside the table
+    const uint4* src = reinterpret_cast<const uint4*>(emb) + (size_t)tok * vec_per_row;
+    uint4* dst = reinterpret_cast<uint4*>(x) + (size_t)m * vec_per_row;
+    for (int i = threadIdx.x; i < vec_per_row; i += blockDim.x) dst[i] = src[i];
+}
+
+hipError_t launch_embedding(const cqil_dims& d, const void* emb, const int32_t* tokens, int M, int vocab, void* x,
+                            hipStream_t st) {
+    const int vpr = d.d_model * (int)esize(d.dtype) / 16;
+    if (d.dtype == CQIL_BF16)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(embedding_kernel<bf16_t>), dim3(M), dim3(256), 0, st, (const bf16_t*)emb,
+                           tokens, (bf16_t*)x, M, vocab, vpr);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(embedding_kernel<float>), dim3(M), dim3(256), 0, st, (const float*)emb,
+                           tokens, (float*)x, M, vocab, vpr);
+    return hipGetLastError();
+}
+
+// logits[b][v] = lm_head[v] . RMSNorm(hidden[b][T-1]) g_final.  grid = (row blocks of the vocabulary, B)
+template <typename T>
+__global__ __launch_bounds__(kThreads) void head_kernel(const T* __restrict__ hidden, const T* __restrict__ g_final,
+                                                         const T* __restrict__ lm_head, float* __restrict__ logits,
+                                                         int T_new, int d_model, int vocab, int rows_per_wg, float eps) {
+    extern __shared__ float smem[];
+    constexpr int V = elem<T>::kVec;
+    float* xs = smem;
+    float* scratch = xs + xs_words(d_model);
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int b = blockIdx.y;
+    const T* x = hidden + ((size_t)b * T_new + (T_new - 1)) * d_model;
+    float ss = 0.f;
+    for (int k = tid; k < d_model; k += kThreads) {
+        const float v = elem<T>::load(x + k);
+        ss += v * v;
+    }
+    ss = block_sum(ss, scratch);
+    const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
+    for (int k = tid; k < d_model; k += kThreads) xs[xs_index<V>(k)] = elem<T>::load(x + k) * r * elem<T>::load(g_final + k);
+    __syncthreads();
+    const int row0 = blockIdx.x * rows_per_wg;
+    const int row1 = min(row0 + rows_per_wg, vocab);
+    for (int o = row0 + 4 * w; o < row1; o += 4 * kWaves) {
+        // the last group of a vocabulary that is not a multiple of 4 re-reads the last row
+        const int o1 = min(o + 1, vocab - 1), o2 = min(o + 2, vocab - 1), o3 = min(o + 3, vocab - 1);
+        float s[4];
+        dot4<T>(lm_head + (size_t)o * d_model, lm_head + (size_t)o1 * d_model, lm_head + (size_t)o2 * d_model,
+                lm_head + (size_t)o3 * d_model, xs, d_model, s);
+        if (lane == 0) {
+            float* out = logits + (size_t)b * vocab;
+            out[o] = s[0];
+            if (o + 1 < vocab) out[o + 1] = s[1];
+            if (o + 2 < vocab) out[o + 2] = s[2];
+            if (o + 3 < vocab) out[o + 3] = s[3];
+        }
+    }
+}
+
+// greedy token: lowest index among the maxima.  One workgroup per sequence.
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int32_t* __restrict__ next, int vocab) {
+    __shared__ float bv[256];
+    __shared__ int bi[256];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const float* lg = logits + (size_t)b * vocab;
+    float best = -INFINITY;
+    int idx = 0x7fffffff;
+    for (int v = tid; v < vocab; v += 256) {
+        const float x = lg[v];
+        if (x > best || (x == best && v < idx)) { best = x; idx = v; }
+    }
+    bv[tid] = best; bi[tid] = idx;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if (tid < s) {
+            const float ov = bv[tid + s];
+            const int oi = bi[tid + s];
+            if (ov > bv[tid] || (ov == bv[tid] && oi < bi[tid])) { bv[tid] = ov; bi[tid] = oi; }
+        }
+        __syncthreads();
+    }
+    if (tid == 0) next[b] = bi[0] == 0x7fffffff ? 0 : bi[0];
+}
+
+hipError_t launch_head(const HeadArgs& h, hipStream_t st) {
+    const int rows = 32;
+    const int xw = (h.d.d_model + 511) & ~511;
+    dim3 grid((h.vocab + rows - 1) / rows, h.B);
+    if (h.d.dtype == CQIL_BF16)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(head_kernel<bf16_t>), grid, dim3(kThreads), (xw + 16) * sizeof(float), st,
+                           (const bf16_t*)h.hidden, (const bf16_t*)h.g_final, (const bf16_t*)h.lm_head, h.logits, h.T,
+                           h.d.d_model, h.vocab, rows, h.d.rms_eps);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(head_kernel<float>), grid, dim3(kThreads), (xw + 16) * sizeof(float), st,
+                           (const float*)h.hidden, (const float*)h.g_final, (const float*)h.lm_head, h.logits, h.T,
+                           h.d.d_model, h.vocab, rows, h.d.rms_eps);
+    if (h.next_token) hipLaunchKernelGGL(argmax_kernel, dim3(h.B), dim3(256), 0, st, h.logits, h.next_token, h.vocab);
+    return hipGetLastError();
+}
+
+}  // namespace cqil

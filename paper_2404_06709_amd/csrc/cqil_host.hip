@@ -1,0 +1,260 @@
+// C ABI of libcqil: argument checking, buffer layouts, the (p, s, e) partition and the model-level loop.
+#include <stdio.h>
+#include <string.h>
+
+#include "cqil_internal.h"
+
+namespace cqil {
+
+static bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int check_dims(const cqil_dims* d, int P) {
+    if (!d) return CQIL_EINVAL;
+    if (P < 1 || P > kMaxP) return CQIL_EINVAL;
+    if (d->dtype != CQIL_F32 && d->dtype != CQIL_BF16) return CQIL_EINVAL;
+    if (d->d_model < 8 || d->n_heads < 1 || d->head_dim < 1 || d->d_ffn < 16 || d->max_seq < 1) return CQIL_EINVAL;
+    if ((long long)d->n_heads * d->head_dim != d->d_model) return CQIL_EINVAL;
+    if (d->d_model % 8 || d->d_ffn % kGuBlock) return CQIL_EINVAL;
+    if (d->d_model > 14336) return CQIL_EINVAL;  // the normalised input of a projection sits in LDS as fp32
+    // lanes sharing one cache slot in the attention kernels: head_dim * esize / 16 must be 4, 8, 16 or 32
+    const int lps = d->head_dim * (int)esize(d->dtype) / 16;
+    if (!pow2(d->head_dim) || lps < 4 || lps > 32) return CQIL_EINVAL;
+    if (!(d->rope_base > 1.0f) || !(d->rms_eps >= 0.0f)) return CQIL_EINVAL;
+    return CQIL_OK;
+}
+
+static int packed_layout(const cqil_dims* d, int P, cqil_packed_layout* L) {
+    int rc = check_dims(d, P);
+    if (rc) return rc;
+    if (!L) return CQIL_EINVAL;
+    const size_t es = esize(d->dtype), dm = d->d_model, f = d->d_ffn;
+    size_t off = 0;
+    L->wqkv = off;   off = align_up(off + (size_t)P * 3 * dm * dm * es);
+    L->wo = off;     off = align_up(off + (size_t)P * dm * dm * es);
+    L->wgu = off;    off = align_up(off + (size_t)P * 2 * f * dm * es);
+    L->wdown = off;  off = align_up(off + (size_t)P * dm * f * es);
+    L->g_attn = off; off = align_up(off + (size_t)P * dm * es);
+    L->g_ffn = off;  off = align_up(off + (size_t)P * dm * es);
+    L->rope = off;   off = align_up(off + (size_t)d->max_seq * (d->head_dim / 2) * 2 * sizeof(float));
+    L->total = off;
+    return CQIL_OK;
+}
+
+int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* W) {
+    int rc = check_dims(d, P);
+    if (rc) return rc;
+    if (B < 1 || T < 1 || !W) return CQIL_EINVAL;
+    if ((long long)B * T > (1ll << 24)) return CQIL_EINVAL;
+    const size_t M = (size_t)B * T, dm = d->d_model, f = d->d_ffn, es = esize(d->dtype);
+    memset(W, 0, sizeof(*W));
+    W->n_chunks = (d->max_seq + kAttnChunk - 1) / kAttnChunk;
+    const size_t K = (size_t)P * f;
+    // K slices of the decode down projection: equal lengths, multiples of 512, at most kDownSliceMax
+    int ns = (int)((K + kDownSliceMax - 1) / kDownSliceMax);
+    size_t sl = ((K + ns - 1) / ns + 511) / 512 * 512;
+    ns = (int)((K + sl - 1) / sl);
+    W->n_slices = ns;
+    W->down_slice = (int)sl;
+    W->n_counters = P * B * d->n_heads + (int)((dm + 31) / 32) + 64;
+    size_t off = 0;
+    W->counters = off;  off = align_up(off + (size_t)W->n_counters * sizeof(int32_t));
+    W->q = off;         off = align_up(off + (size_t)P * M * dm * sizeof(float));
+    W->ctx = off;       off = align_up(off + (size_t)P * M * dm * sizeof(float));
+    W->attn_part = off; off = align_up(off + (size_t)P * B * d->n_heads * W->n_chunks * (d->head_dim + 2) * sizeof(float));
+    W->a = off;         off = align_up(off + (size_t)P * M * dm * sizeof(float));
+    if (M == 1) {
+        W->u = off;         off = align_up(off + K * sizeof(float));
+        W->down_part = off; off = align_up(off + (size_t)ns * dm * sizeof(float));
+    } else {
+        W->nrm = off;     off = align_up(off + (size_t)P * M * dm * es);
+        W->qkv = off;     off = align_up(off + M * (size_t)P * 3 * dm * es);
+        W->ctx_act = off; off = align_up(off + (size_t)P * M * dm * es);
+        W->resid = off;   off = align_up(off + M * dm * sizeof(float));
+        W->gu = off;      off = align_up(off + M * (size_t)P * 2 * f * es);
+        W->u_act = off;   off = align_up(off + M * K * es);
+    }
+    W->total = off;
+    return CQIL_OK;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace cqil
+
+using namespace cqil;
+
+extern "C" {
+
+const char* cqil_version(void) { return "cqil-mi355x 0.1 (gfx950)"; }
+
+const char* cqil_strerror(int status) {
+    switch (status) {
+        case CQIL_OK: return "ok";
+        case CQIL_EINVAL: return "invalid argument";
+        case CQIL_ESIZE: return "buffer too small";
+        case CQIL_ERANGE: return "sequence or batch out of range";
+        case CQIL_EHIP: return "HIP launch failure";
+        default: return "unknown status";
+    }
+}
+
+int cqil_packed_layout_of(const cqil_dims* dims, int P, cqil_packed_layout* out) { return packed_layout(dims, P, out); }
+
+size_t cqil_packed_bytes(const cqil_dims* dims, int P) {
+    cqil_packed_layout L;
+    return packed_layout(dims, P, &L) ? 0 : L.total;
+}
+
+size_t cqil_workspace_bytes(const cqil_dims* dims, int P, int B, int T) {
+    WsLayout W;
+    return ws_layout(dims, P, B, T, &W) ? 0 : W.total;
+}
+
+size_t cqil_workspace_attn_out_offset(const cqil_dims* dims, int P, int B, int T) {
+    WsLayout W;
+    return ws_layout(dims, P, B, T, &W) ? (size_t)-1 : W.a;
+}
+
+int cqil_partition(int L, int p, int s, int e, int* group_sizes_out, int* n_groups_out) {
+    if (!group_sizes_out || !n_groups_out) return CQIL_EINVAL;
+    if (L < 1 || p < 1 || s < 1 || e > L || s > e + 1) return CQIL_EINVAL;
+    int n = 0;
+    for (int l = 1; l <= L;) {
+        int sz = 1;
+        if (l >= s && l <= e) {
+            const int left = e - l + 1;
+            sz = left < p ? left : p;
+        }
+        group_sizes_out[n++] = sz;
+        l += sz;
+    }
+    *n_groups_out = n;
+    return CQIL_OK;
+}
+
+int cqil_pack_group(const cqil_dims* dims, int P, const cqil_layer* layers, void* packed, size_t packed_bytes,
+                    void* stream) {
+    cqil_packed_layout L;
+    int rc = packed_layout(dims, P, &L);
+    if (rc) return rc;
+    if (!layers || !packed) return CQIL_EINVAL;
+    if (!aligned16(packed)) return CQIL_EINVAL;
+    if (packed_bytes < L.total) return CQIL_ESIZE;
+    PackArgs pa;
+    for (int l = 0; l < P; ++l) {
+        const cqil_layer& s = layers[l];
+        const void* ptrs[9] = {s.wq, s.wk, s.wv, s.wo, s.wgate, s.wup, s.wdown, s.g_attn, s.g_ffn};
+        for (const void* p : ptrs)
+            if (!p || !aligned16(p)) return CQIL_EINVAL;
+        pa.layers[l] = s;
+    }
+    hipError_t e = launch_pack(*dims, P, pa, (char*)packed, L, (hipStream_t)stream);
+    return e == hipSuccess ? CQIL_OK : CQIL_EHIP;
+}
+
+static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const void* packed, void* kc, void* vc,
+                              int32_t* kv_len, int b_max, int max_kv_len, const void* x_in, void* x_out, int B, int T,
+                              int advance, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    StepArgs a;
+    int rc = packed_layout(dims, P, &a.pl);
+    if (rc) return rc;
+    if (bypass_d < 0 || B < 1 || T < 1) return CQIL_EINVAL;
+    if (!packed || !kc || !vc || !kv_len || !x_in || !x_out || !workspace) return CQIL_EINVAL;
+    if (!aligned16(packed) || !aligned16(kc) || !aligned16(vc) || !aligned16(x_in) || !aligned16(x_out) ||
+        !aligned16(workspace))
+        return CQIL_EINVAL;
+    if (b_max < 1 || max_kv_len < 0) return CQIL_EINVAL;
+    if (B > b_max) return CQIL_ERANGE;
+    if ((long long)max_kv_len + T > dims->max_seq) return CQIL_ERANGE;
+    rc = ws_layout(dims, P, B, T, &a.wl);
+    if (rc) return rc;
+    if (workspace_bytes < a.wl.total) return CQIL_ESIZE;
+    a.d = *dims; a.P = P; a.bypass_d = bypass_d; a.B = B; a.T = T; a.advance = advance ? 1 : 0;
+    a.packed = (const char*)packed;
+    a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.b_max = b_max; a.max_kv_len = max_kv_len;
+    a.x_in = x_in; a.x_out = x_out; a.ws = (char*)workspace;
+    hipError_t e = (B * T == 1) ? launch_decode_step(a, st) : launch_generic_step(a, st);
+    return e == hipSuccess ? CQIL_OK : CQIL_EHIP;
+}
+
+int cqil_group_forward(const cqil_dims* dims, int P, int bypass_d, const void* packed, cqil_kv* kv, const void* x_in,
+                       void* x_out, int B, int T, int advance_kv_len, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    if (!kv) return CQIL_EINVAL;
+    int rc = group_forward_impl(dims, P, bypass_d, packed, kv->k, kv->v, kv->kv_len, kv->b_max, kv->max_kv_len, x_in,
+                                x_out, B, T, advance_kv_len, workspace, workspace_bytes, (hipStream_t)stream);
+    if (rc == CQIL_OK && advance_kv_len) kv->max_kv_len += T;
+    return rc;
+}
+
+// Model workspace: [x ping][x pong? no: groups run in place][logits][argmax scratch][group workspace]
+static int model_ws(const cqil_model* m, int B, int T, size_t* x_off, size_t* logits_off, size_t* scratch_off,
+                    size_t* group_off, size_t* total) {
+    if (!m || !m->group_sizes || m->n_groups < 1 || m->vocab < 1 || B < 1 || T < 1) return CQIL_EINVAL;
+    size_t gmax = 0;
+    for (int g = 0; g < m->n_groups; ++g) {
+        WsLayout W;
+        int rc = ws_layout(&m->dims, m->group_sizes[g], B, T, &W);
+        if (rc) return rc;
+        if (W.total > gmax) gmax = W.total;
+    }
+    size_t off = 0;
+    *x_off = off;       off = align_up(off + (size_t)B * T * m->dims.d_model * esize(m->dims.dtype));
+    *logits_off = off;  off = align_up(off + (size_t)B * m->vocab * sizeof(float));
+    *scratch_off = off; off = align_up(off + (size_t)B * 1024 * 2 * sizeof(float));
+    *group_off = off;   off = align_up(off + gmax);
+    *total = off;
+    return CQIL_OK;
+}
+
+size_t cqil_model_workspace_bytes(const cqil_model* m, int B, int T) {
+    size_t a, b, c, d, t;
+    return model_ws(m, B, T, &a, &b, &c, &d, &t) ? 0 : t;
+}
+
+int cqil_model_forward(cqil_model* m, const int32_t* tokens, int B, int T, int bypass_d, int advance_kv_len,
+                       void* hidden_out, float* logits_out, int32_t* next_token_out, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+    size_t x_off, lg_off, sc_off, g_off, total;
+    int rc = model_ws(m, B, T, &x_off, &lg_off, &sc_off, &g_off, &total);
+    if (rc) return rc;
+    if (!tokens || !workspace || !m->packed || !m->k_cache || !m->v_cache || !m->kv_len || !m->embedding ||
+        !m->g_final || !m->lm_head)
+        return CQIL_EINVAL;
+    if (bypass_d < 0) return CQIL_EINVAL;
+    if (!aligned16(workspace) || !aligned16(m->embedding) || !aligned16(m->lm_head) || !aligned16(m->g_final))
+        return CQIL_EINVAL;
+    if (hidden_out && !aligned16(hidden_out)) return CQIL_EINVAL;
+    if (workspace_bytes < total) return CQIL_ESIZE;
+    if (B > m->b_max) return CQIL_ERANGE;
+    if ((long long)m->max_kv_len + T > m->dims.max_seq) return CQIL_ERANGE;
+    for (int g = 0; g < m->n_groups; ++g)
+        if (!m->packed[g] || !m->k_cache[g] || !m->v_cache[g]) return CQIL_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    void* x = hidden_out ? hidden_out : (void*)(ws + x_off);
+    const size_t gbytes = total - g_off;
+
+    if (launch_embedding(m->dims, m->embedding, tokens, B * T, m->vocab, x, st) != hipSuccess) return CQIL_EHIP;
+    for (int g = 0; g < m->n_groups; ++g) {
+        rc = group_forward_impl(&m->dims, m->group_sizes[g], bypass_d, m->packed[g], m->k_cache[g], m->v_cache[g],
+                                m->kv_len, m->b_max, m->max_kv_len, x, x, B, T, 0, ws + g_off, gbytes, st);
+        if (rc) return rc;
+    }
+    if (logits_out || next_token_out) {
+        HeadArgs h;
+        h.d = m->dims; h.vocab = m->vocab; h.B = B; h.T = T;
+        h.hidden = x; h.g_final = m->g_final; h.lm_head = m->lm_head;
+        h.logits = logits_out ? logits_out : (float*)(ws + lg_off);
+        h.next_token = next_token_out;
+        h.ws = ws + sc_off;
+        if (launch_head(h, st) != hipSuccess) return CQIL_EHIP;
+    }
+    if (advance_kv_len) {
+        if (launch_advance(m->kv_len, B, T, st) != hipSuccess) return CQIL_EHIP;
+        m->max_kv_len += T;
+    }
+    return CQIL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Host-side internals of libcqil: buffer layouts and kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/cqil.h"
+
+namespace cqil {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+inline size_t esize(int dtype) { return dtype == CQIL_BF16 ? 2 : 4; }
+
+constexpr int kGuBlock = 16;        // gate/up rows are interleaved in blocks of this many rows
+constexpr int kAttnChunk = 128;     // KV slots per workgroup of the split-KV decode attention
+constexpr int kDownSliceMax = 8192; // longest K slice of the decode down projection (fp32 words of LDS)
+constexpr int kMaxP = 16;
+
+// Workspace of one group step.  Offsets in bytes, all multiples of 256.
+struct WsLayout {
+    // decode fast path (B*T == 1) and shared
+    size_t counters;   // int32 [n_counters]      arrival counters (zeroed by the first kernel of a step)
+    size_t q;          // f32 [P][M][d_model]     rotated queries
+    size_t ctx;        // f32 [P][M][d_model]     attention context (heads concatenated)
+    size_t attn_part;  // f32 [P*B*n_heads][n_chunks][head_dim+2]  split-KV partials (max, sum, context)
+    size_t a;          // f32 [P][M][d_model]     attention outputs a_i
+    size_t u;          // f32 [M][P*d_ffn]        SwiGLU outputs (decode path)
+    size_t down_part;  // f32 [n_slices][d_model] split-K partials of the down projection
+    // token-parallel path (M = B*T > 1); act = dtype of the call
+    size_t nrm;        // act [P][M][d_model]     normalised inputs (attention norm, later FFN norm)
+    size_t qkv;        // act [M][P*3*d_model]
+    size_t ctx_act;    // act [P][M][d_model]
+    size_t resid;      // f32 [M][d_model]        x + sum_i a_i
+    size_t gu;         // act [M][P*2*d_ffn]
+    size_t u_act;      // act [M][P*d_ffn]
+    size_t total;
+    int n_counters, n_chunks, n_slices, down_slice;
+};
+
+int check_dims(const cqil_dims* d, int P);
+int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* out);
+
+struct PackArgs {
+    cqil_layer layers[kMaxP];
+};
+
+// launchers; every one returns a hipError_t from the launch
+hipError_t launch_pack(const cqil_dims& d, int P, const PackArgs& src, char* packed, const cqil_packed_layout& L,
+                       hipStream_t st);
+
+struct StepArgs {
+    cqil_dims d;
+    int P, bypass_d, B, T, advance;
+    const char* packed;
+    cqil_packed_layout pl;
+    void *kc, *vc;
+    int32_t* kv_len;
+    int b_max, max_kv_len;
+    const void* x_in;
+    void* x_out;
+    char* ws;
+    WsLayout wl;
+};
+
+hipError_t launch_decode_step(const StepArgs& a, hipStream_t st);   // B*T == 1
+hipError_t launch_generic_step(const StepArgs& a, hipStream_t st);  // any B, T
+
+struct HeadArgs {
+    cqil_dims d;
+    int vocab, B, T;
+    const void* hidden;   // act [B][T][d_model]
+    const void* g_final;  // [d_model]
+    const void* lm_head;  // [vocab][d_model]
+    float* logits;        // [B][vocab] (workspace if the caller passed none)
+    int32_t* next_token;  // [B] or null
+    char* ws;             // scratch for the argmax partials
+};
+hipError_t launch_embedding(const cqil_dims& d, const void* emb, const int32_t* tokens, int M, int vocab, void* x,
+                            hipStream_t st);
+hipError_t launch_head(const HeadArgs& a, hipStream_t st);
+hipError_t launch_advance(int32_t* kv_len, int B, int T, hipStream_t st);
+
+}  // namespace cqil

@@ -1,0 +1,154 @@
+"""Host-side checks of the C ABI that need no GPU: exported symbols, argument validation, size
+arithmetic and the partition rule."""
+import ctypes as C
+import os
+import re
+
+import pytest
+import torch
+
+import oracle as orc
+from paper_2404_06709_amd import binding as cq
+from paper_2404_06709_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def dims(shape="tiny", dtype=torch.float32, max_seq=64):
+    s = synth.SHAPES[shape]
+    return cq.make_dims(s.d_model, s.n_heads, s.head_dim, s.d_ffn, max_seq, dtype)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "cqil.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(cqil_[a-z_]+)\s*\(", hdr))
+    assert {"cqil_pack_group", "cqil_group_forward", "cqil_model_forward", "cqil_partition"} <= names
+    L = cq.lib()
+    for n in sorted(names):
+        assert hasattr(L, n), f"{n} is declared in cqil.h but not exported"
+    assert "gfx950" in cq.version()
+
+
+def test_strerror_covers_all_codes():
+    texts = {cq.strerror(c) for c in (0, -1, -2, -3, -4)}
+    assert len(texts) == 5 and "unknown" not in " ".join(texts)
+    assert "unknown" in cq.strerror(-99)
+
+
+def test_packed_layout_arithmetic():
+    for shape, dt, P in (("tiny", torch.float32, 2), ("7b", torch.bfloat16, 4), ("33b", torch.bfloat16, 4)):
+        d = dims(shape, dt, 2048)
+        s = synth.SHAPES[shape]
+        es = 4 if dt == torch.float32 else 2
+        L = cq.cqil_packed_layout_of(d, P)
+        params = P * (4 * s.d_model ** 2 + 3 * s.d_model * s.d_ffn)
+        assert L.wqkv == 0
+        assert L.wo - L.wqkv >= P * 3 * s.d_model ** 2 * es
+        assert L.wgu - L.wo >= P * s.d_model ** 2 * es
+        assert L.wdown - L.wgu >= P * 2 * s.d_ffn * s.d_model * es
+        assert L.g_attn - L.wdown >= P * s.d_ffn * s.d_model * es
+        assert L.rope - L.g_ffn >= P * s.d_model * es
+        extra = 2 * P * s.d_model * es + 2048 * (s.head_dim // 2) * 8
+        assert params * es + extra <= L.total <= params * es + extra + 7 * 256
+        for off in (L.wo, L.wgu, L.wdown, L.g_attn, L.g_ffn, L.rope, L.total):
+            assert off % 256 == 0
+        assert cq.cqil_packed_bytes(d, P) == L.total
+    # the weight bytes of the headline configuration: 4.280 GB for one 33B-shaped group of four
+    d = dims("33b", torch.bfloat16, 2048)
+    L = cq.cqil_packed_layout_of(d, 4)
+    assert L.g_attn == 4 * 535_035_904 * 2
+
+
+@pytest.mark.parametrize("field,value", [("d_model", 250), ("n_heads", 3), ("head_dim", 48), ("d_ffn", 690),
+                                         ("max_seq", 0), ("dtype", 7), ("rope_base", 0.5), ("rms_eps", -1.0)])
+def test_bad_dims_are_rejected(field, value):
+    d = dims()
+    setattr(d, field, value)
+    assert cq.cqil_packed_bytes(d, 2) == 0
+    assert cq.cqil_workspace_bytes(d, 2, 1, 1) == 0
+    out = cq.cqil_packed_layout()
+    assert cq.lib().cqil_packed_layout_of(C.byref(d), 2, C.byref(out)) == cq.CQIL_EINVAL
+
+
+def test_bad_group_sizes_and_counts():
+    d = dims()
+    assert cq.cqil_packed_bytes(d, 0) == 0 and cq.cqil_packed_bytes(d, 17) == 0
+    assert cq.cqil_workspace_bytes(d, 2, 0, 1) == 0 and cq.cqil_workspace_bytes(d, 2, 1, 0) == 0
+    assert cq.cqil_workspace_bytes(d, 2, 1, 1) > 0
+    assert cq.cqil_workspace_bytes(d, 2, 2, 5) > cq.cqil_workspace_bytes(d, 2, 1, 1)
+
+
+def _call_group(d, P=2, bypass=1, packed=0x1000, k=0x1000, v=0x1000, kvl=0x1000, x=0x1000, y=0x1000, B=1, T=1,
+                ws=0x1000, ws_bytes=1 << 40, b_max=1, max_kv=0):
+    kv = cq.cqil_kv(k, v, kvl, b_max, max_kv)
+    return cq.lib().cqil_group_forward(C.byref(d), P, bypass, packed, C.byref(kv), x, y, B, T, 0, ws, ws_bytes, None)
+
+
+def test_group_forward_validates_before_launching():
+    """Every call below must fail on the host: the fake pointers are never dereferenced."""
+    d = dims(max_seq=64)
+    assert _call_group(d, bypass=-1) == cq.CQIL_EINVAL
+    assert _call_group(d, P=0) == cq.CQIL_EINVAL
+    assert _call_group(d, packed=None) == cq.CQIL_EINVAL
+    assert _call_group(d, x=None) == cq.CQIL_EINVAL
+    assert _call_group(d, ws=None) == cq.CQIL_EINVAL
+    assert _call_group(d, x=0x1004) == cq.CQIL_EINVAL                 # misaligned
+    assert _call_group(d, B=0) == cq.CQIL_EINVAL
+    assert _call_group(d, B=2, b_max=1) == cq.CQIL_ERANGE
+    assert _call_group(d, max_kv=64) == cq.CQIL_ERANGE                # 64 cached + 1 new > max_seq 64
+    assert _call_group(d, T=8, max_kv=60) == cq.CQIL_ERANGE
+    assert _call_group(d, ws_bytes=16) == cq.CQIL_ESIZE
+    assert cq.lib().cqil_group_forward(C.byref(d), 2, 1, 0x1000, None, 0x1000, 0x1000, 1, 1, 0, 0x1000, 1 << 40,
+                                       None) == cq.CQIL_EINVAL
+
+
+def test_pack_group_validates_before_launching():
+    d = dims()
+    L = (cq.cqil_layer * 2)()
+    for i in range(2):
+        for f, _ in cq.cqil_layer._fields_:
+            setattr(L[i], f, 0x1000)
+    need = cq.cqil_packed_bytes(d, 2)
+    lib = cq.lib()
+    assert lib.cqil_pack_group(C.byref(d), 2, L, 0x1000, need - 1, None) == cq.CQIL_ESIZE
+    assert lib.cqil_pack_group(C.byref(d), 2, None, 0x1000, need, None) == cq.CQIL_EINVAL
+    assert lib.cqil_pack_group(C.byref(d), 2, L, None, need, None) == cq.CQIL_EINVAL
+    L[1].wup = 0
+    assert lib.cqil_pack_group(C.byref(d), 2, L, 0x1000, need, None) == cq.CQIL_EINVAL
+    L[1].wup = 0x1008
+    assert lib.cqil_pack_group(C.byref(d), 2, L, 0x1000, need, None) == cq.CQIL_EINVAL
+
+
+def test_partition_agrees_with_the_paper_and_the_oracle():
+    assert cq.cqil_partition(32, 2, 9, 30) == [1] * 8 + [2] * 11 + [1] * 2      # Sec.4.2 worked example
+    assert cq.cqil_partition(60, 4, 19, 58) == [1] * 18 + [4] * 10 + [1] * 2    # main table, 33B, p=4
+    assert cq.cqil_partition(60, 4, 21, 60) == [1] * 20 + [4] * 10
+    for L in (1, 5, 12):
+        for p in (1, 2, 3, 4):
+            for s in range(1, L + 1):
+                for e in range(s, L + 1):
+                    assert cq.cqil_partition(L, p, s, e) == orc.partition(L, p, s, e)
+    for bad in ((4, 2, 0, 4), (4, 2, 1, 5), (4, 0, 1, 4), (0, 1, 1, 1)):
+        with pytest.raises(cq.CqilError):
+            cq.cqil_partition(*bad)
+
+
+def test_model_forward_validates_before_launching():
+    d = dims()
+    n = 2
+    gs = (C.c_int * n)(2, 2)
+    ptrs = (C.c_void_p * n)(0x1000, 0x1000)
+    m = cq.cqil_model(d, 100, n, gs, ptrs, ptrs, ptrs, 0x1000, 1, 0, 0x1000, 0x1000, 0x1000)
+    lib = cq.lib()
+    need = lib.cqil_model_workspace_bytes(C.byref(m), 1, 4)
+    assert need > cq.cqil_workspace_bytes(d, 2, 1, 4)
+    assert lib.cqil_model_forward(C.byref(m), 0x1000, 1, 4, 1, 0, None, None, None, 0x1000, need - 1, None) == cq.CQIL_ESIZE
+    assert lib.cqil_model_forward(C.byref(m), None, 1, 4, 1, 0, None, None, None, 0x1000, need, None) == cq.CQIL_EINVAL
+    assert lib.cqil_model_forward(C.byref(m), 0x1000, 2, 4, 1, 0, None, None, None, 0x1000, 1 << 40, None) == cq.CQIL_ERANGE
+    m.max_kv_len = 62
+    assert lib.cqil_model_forward(C.byref(m), 0x1000, 1, 4, 1, 0, None, None, None, 0x1000, need, None) == cq.CQIL_ERANGE
+    m.max_kv_len = 0
+    assert lib.cqil_model_forward(C.byref(m), 0x1000, 1, 4, -1, 0, None, None, None, 0x1000, need, None) == cq.CQIL_EINVAL
+    gs[1] = 0
+    assert lib.cqil_model_workspace_bytes(C.byref(m), 1, 4) == 0

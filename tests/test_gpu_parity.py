@@ -1,0 +1,251 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2404_06709_amd import binding as cq
+from paper_2404_06709_amd import runtime as rt
+from paper_2404_06709_amd import synth
+from parity_util import TOL, Pair, gdims, odims, rel_err, say
+
+pytestmark = pytest.mark.gpu
+
+TINY = synth.SHAPES["tiny"]
+MID = synth.Shape(512, 4, 128, 1024)        # head_dim 128 like the LLaMA shapes, still small
+ODD = synth.Shape(384, 6, 64, 1040)         # d_model not a multiple of 512, d_ffn = 16 * 65
+WIDE = synth.Shape(256, 4, 64, 2752)        # P=4 gives a down-projection K of 11008: two K slices
+
+
+# ------------------------------------------------------------------------------------------ packing
+def _pattern_layers(shape, P, dtype):
+    """Weights whose bit patterns identify (layer, matrix, row, column)."""
+    layers = []
+    for l in range(P):
+        L = {}
+        for m, (name, rows, cols) in enumerate((("wq", shape.d_model, shape.d_model), ("wk", shape.d_model, shape.d_model),
+                                                ("wv", shape.d_model, shape.d_model), ("wo", shape.d_model, shape.d_model),
+                                                ("wgate", shape.d_ffn, shape.d_model), ("wup", shape.d_ffn, shape.d_model),
+                                                ("wdown", shape.d_model, shape.d_ffn), ("g_attn", 1, shape.d_model),
+                                                ("g_ffn", 1, shape.d_model))):
+            r = torch.arange(rows, dtype=torch.int64)[:, None]
+            c = torch.arange(cols, dtype=torch.int64)[None, :]
+            if dtype == torch.float32:
+                bits = (((l * 9 + m) << 26) + r * cols + c).to(torch.int32)
+                t = bits.view(torch.float32)
+            else:
+                bits = ((r * 131 + c * 7 + m * 9973 + l * 31337) & 0xFFFF).to(torch.int32)
+                bits = torch.where(bits >= 32768, bits - 65536, bits).to(torch.int16)
+                t = bits.view(torch.bfloat16)
+            L[name] = t.reshape(-1) if rows == 1 else t.contiguous()
+        layers.append(L)
+    return layers
+
+
+def _bits(t):
+    t = t.detach().cpu().contiguous()
+    return t.view(torch.int32).numpy() if t.dtype == torch.float32 else t.view(torch.int16).numpy()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape,P", [(TINY, 2), (ODD, 3), (MID, 1)])
+def test_pack_group_is_a_bit_exact_index_map(shape, P, dtype):
+    max_seq = 96
+    d = gdims(shape, max_seq, dtype)
+    layers = _pattern_layers(shape, P, dtype)
+    dev = rt.to_device(layers)
+    lay = cq.cqil_packed_layout_of(d, P)
+    packed = torch.full((lay.total,), 0xAB, dtype=torch.uint8, device="cuda")
+    cq.cqil_pack_group(d, dev, packed)
+    torch.cuda.synchronize()
+    raw = packed.cpu()
+    es = 4 if dtype == torch.float32 else 2
+    npdt = np.int32 if dtype == torch.float32 else np.int16
+    dm, f = shape.d_model, shape.d_ffn
+
+    def region(off, n):
+        return raw[off: off + n * es].numpy().view(npdt)
+
+    src = [{k: _bits(v) for k, v in L.items()} for L in layers]
+    exp_qkv = np.concatenate([np.concatenate([s["wq"], s["wk"], s["wv"]], axis=0) for s in src], axis=0)
+    np.testing.assert_array_equal(region(lay.wqkv, P * 3 * dm * dm).reshape(P * 3 * dm, dm), exp_qkv)
+    exp_wo = np.stack([s["wo"] for s in src], axis=1)                       # [o][l][k]
+    np.testing.assert_array_equal(region(lay.wo, P * dm * dm).reshape(dm, P, dm), exp_wo)
+    exp_gu = np.stack([np.stack([s["wgate"].reshape(f // 16, 16, dm), s["wup"].reshape(f // 16, 16, dm)], axis=1)
+                       for s in src], axis=0)                               # [l][blk][gate|up][16][k]
+    np.testing.assert_array_equal(region(lay.wgu, P * 2 * f * dm).reshape(P, f // 16, 2, 16, dm), exp_gu)
+    exp_down = np.stack([s["wdown"] for s in src], axis=1)                  # [o][l][j]
+    np.testing.assert_array_equal(region(lay.wdown, P * dm * f).reshape(dm, P, f), exp_down)
+    np.testing.assert_array_equal(region(lay.g_attn, P * dm).reshape(P, dm), np.stack([s["g_attn"] for s in src]))
+    np.testing.assert_array_equal(region(lay.g_ffn, P * dm).reshape(P, dm), np.stack([s["g_ffn"] for s in src]))
+    # rotary table: (cos, sin)(pos * base^(-2i/d)), fp32 roundings of the double values
+    half = shape.head_dim // 2
+    table = raw[lay.rope: lay.rope + max_seq * half * 8].numpy().view(np.float32).reshape(max_seq, half, 2)
+    phi = np.arange(max_seq)[:, None] * 10000.0 ** (-2.0 * np.arange(half)[None, :] / shape.head_dim)
+    np.testing.assert_allclose(table[..., 0], np.cos(phi), atol=1.2e-7, rtol=0)
+    np.testing.assert_allclose(table[..., 1], np.sin(phi), atol=1.2e-7, rtol=0)
+    # alignment gaps between the parts are not written
+    ends = [(lay.wqkv + P * 3 * dm * dm * es, lay.wo), (lay.wo + P * dm * dm * es, lay.wgu),
+            (lay.wgu + P * 2 * f * dm * es, lay.wdown), (lay.wdown + P * dm * f * es, lay.g_attn),
+            (lay.g_attn + P * dm * es, lay.g_ffn), (lay.g_ffn + P * dm * es, lay.rope),
+            (lay.rope + max_seq * half * 8, lay.total)]
+    for a, b in ends:
+        assert (raw[a:b] == 0xAB).all()
+
+
+# ------------------------------------------------------------------------------------------ decode, one token
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [TINY, MID, ODD, WIDE])
+def test_decode_step_matches_oracle(shape, dtype):
+    """Single-token decode (the bandwidth-bound path) over cache lengths that straddle the split-KV chunk
+    boundaries, group sizes 1..4 and every bypass distance."""
+    for P, ds in ((1, (0, 2)), (2, (0, 1)), (4, (0, 1, 2, 3, 7))):
+        pair = Pair(shape, P, dtype, max_seq=400, b_max=1, seed=1001 + P, w_std=0.05, gain_jitter=0.1)
+        for S in (0, 1, 127, 128, 129, 390):
+            pair.okc[:] = 0; pair.ovc[:] = 0
+            pair.group.k.zero_(); pair.group.v.zero_()
+            pair.fill_cache([S], seed=50 + S)
+            for i, d in enumerate(ds):
+                pair.set_lens([S])
+                pair.step(pair.hidden(1, 1, seed=7 + i), d, label=f"decode {dtype} P={P} S={S}")
+
+
+def test_decode_is_deterministic_and_in_place():
+    pair = Pair(TINY, 4, torch.float32, max_seq=300, b_max=1, seed=5, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([260], seed=9)
+    x = pair.hidden(1, 1, seed=3).cuda()
+    outs = []
+    for _ in range(3):
+        pair.set_lens([260])
+        outs.append(pair.group.forward(x, 1, advance=False).clone())
+    buf = x.clone()
+    pair.group.forward(buf, 1, advance=False, out=buf)          # x_out aliases x_in
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2]) and torch.equal(outs[0], buf)
+    assert pair.group.kv_len.cpu()[0].item() == 260             # advance=False leaves the length alone
+
+
+# ------------------------------------------------------------------------------------------ prefill / batch
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [TINY, ODD])
+def test_token_parallel_path_matches_oracle(shape, dtype):
+    pair = Pair(shape, 3, dtype, max_seq=200, b_max=4, seed=77, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([0, 7, 130], seed=5)
+    pair.step(pair.hidden(3, 5, seed=1), 1, label=f"prefill {dtype}")      # ragged lengths, T > 1
+    pair.step(pair.hidden(3, 1, seed=2), 2, label=f"batched decode {dtype}")
+    pair.step(pair.hidden(1, 67, seed=3), 0, label=f"long chunk {dtype}")  # more than one 64-row tile, ragged
+
+
+def test_prefill_then_decode_equals_one_prefill():
+    """Property that holds at any size: prefilling T tokens equals prefilling T-1 and decoding one."""
+    pair = Pair(TINY, 2, torch.float32, max_seq=64, b_max=1, seed=11, w_std=0.05, gain_jitter=0.1)
+    x = pair.hidden(1, 9, seed=4)
+    g = pair.group
+    g.set_kv_len([0])
+    full = g.forward(x.cuda(), 1).cpu()
+    k_full = g.k.clone()
+    g.k.zero_(); g.v.zero_(); g.set_kv_len([0])
+    head = g.forward(x[:, :8].cuda(), 1).cpu()
+    tail = g.forward(x[:, 8:].cuda(), 1).cpu()
+    assert rel_err(head.numpy(), full[:, :8].numpy()) < 1e-5
+    assert rel_err(tail.numpy(), full[:, 8:].numpy()) < 1e-5
+    assert rel_err(g.k.cpu().numpy(), k_full.cpu().numpy()) < 1e-5
+
+
+# ------------------------------------------------------------------------------------------ configuration 1
+@pytest.mark.parametrize("d", [0, 1])
+def test_config1_tiny_two_groups_prefill_32_then_16_decode_steps(d):
+    """Tiny fp32 decoder, 4 layers as 2 groups of P=2, weights N(0,0.02), gains 1: a 32-token prefill of
+    N(0,1) hidden states, then 16 decode steps; each side chains its own two groups."""
+    dtype = torch.float32
+    pairs = [Pair(TINY, 2, dtype, max_seq=64, b_max=1, seed=1001 + g) for g in range(2)]
+    gen = synth.generator(4242)
+    worst = 0.0
+    for step in range(17):
+        T = 32 if step == 0 else 1
+        x = synth.normal((1, T, TINY.d_model), 1.0, dtype, gen)
+        y_gpu, y_ref = x, synth.widen(x)
+        # teacher forcing between the groups: the second group of both sides reads the oracle's state
+        # rounded to the storage type, so that an error of group 1 is not judged twice
+        y_gpu, y_ref = pairs[0].step(x, d, label=f"cfg1 step {step} group 0")
+        x2 = torch.from_numpy(y_ref).to(dtype)
+        y_gpu2, y_ref2 = pairs[1].step(x2, d, label=f"cfg1 step {step} group 1")
+        worst = max(worst, rel_err(synth.widen(y_gpu2), y_ref2))
+    assert worst <= TOL[dtype]
+
+
+def _tiny_model(dtype, group_sizes, vocab, max_seq, seed, w_std=0.05):
+    L = sum(group_sizes)
+    layers = synth.make_layers(L, TINY, dtype, seed, w_std=w_std, gain_jitter=0.1)
+    gen = synth.generator(seed + 1)
+    emb = synth.normal((vocab, TINY.d_model), 1.0, dtype, gen)
+    head = synth.normal((vocab, TINY.d_model), 0.05, dtype, gen)
+    gfin = (1.0 + synth.normal((TINY.d_model,), 0.1, torch.float32, gen)).to(dtype)
+    gd = gdims(TINY, max_seq, dtype)
+    groups, l0 = [], 0
+    for P in group_sizes:
+        groups.append(rt.Group(gd, rt.to_device(layers[l0:l0 + P]), b_max=1))
+        l0 += P
+    kv_len = torch.zeros(1, dtype=torch.int32, device="cuda")
+    model = cq.Model(gd, group_sizes, [g.packed for g in groups], [g.k for g in groups], [g.v for g in groups], kv_len,
+                     emb.cuda(), gfin.cuda(), head.cuda())
+    np_layers = [synth.layer_to_numpy(x) for x in layers]
+    return model, groups, kv_len, np_layers, synth.to_numpy(emb), synth.to_numpy(gfin), synth.to_numpy(head)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_model_forward_teacher_forced(dtype):
+    """cqil_model_forward on a tiny 6-layer model, partition (p=2, s=2, e=5): prefill 12 tokens, then
+    8 greedy steps fed with the ORACLE's tokens; logits compared at every step."""
+    vocab, max_seq = 1003, 48
+    sizes = cq.cqil_partition(6, 2, 2, 5)
+    assert sizes == [1, 2, 2, 1]
+    model, groups, kv_len, nl, emb, gfin, head = _tiny_model(dtype, sizes, vocab, max_seq, seed=300)
+    od = odims(TINY, max_seq, dtype)
+    okc, ovc = orc.new_cache(6, 1, od), orc.new_cache(6, 1, od)
+    tokens = torch.randint(0, vocab, (1, 12), generator=synth.generator(8)).to(torch.int32)
+    olen = 0
+    agree = 0
+    for step in range(9):
+        T = tokens.shape[1]
+        ws = torch.empty(cq.cqil_model_workspace_bytes(model, 1, T), dtype=torch.uint8, device="cuda")
+        logits = torch.empty(1, vocab, dtype=torch.float32, device="cuda")
+        nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+        hid = torch.empty(1, T, TINY.d_model, dtype=dtype, device="cuda")
+        cq.cqil_model_forward(model, tokens.cuda(), 1, T, 1, True, hid, logits, nxt, ws)
+        torch.cuda.synchronize()
+        ref = orc.model_forward(od, nl, sizes, 1, emb, gfin, head, okc, ovc, [olen], tokens.numpy())
+        olen += T
+        e_h = rel_err(synth.widen(hid.cpu()), ref["hidden"])
+        e_l = rel_err(logits.cpu().numpy(), ref["logits"])
+        say(f"  model {dtype} step {step}: hidden {e_h:.2e} logits {e_l:.2e}")
+        # six layers in a row: the per-group tolerance compounds, allow the sum over group steps
+        assert e_h <= 4 * TOL[dtype] and e_l <= 4 * TOL[dtype]
+        top2 = np.sort(ref["logits"][0])[-2:]
+        if top2[1] - top2[0] > 8 * TOL[dtype] * np.abs(ref["logits"]).max():
+            assert nxt.cpu()[0].item() == ref["next"][0]
+        agree += int(nxt.cpu()[0].item() == ref["next"][0])
+        assert kv_len.cpu()[0].item() == olen and model.c.max_kv_len == olen
+        tokens = torch.from_numpy(ref["next"].reshape(1, 1).astype(np.int32))
+    say(f"  greedy tokens agreeing with the oracle: {agree}/9")
+
+
+def test_model_forward_equals_chain_of_group_calls():
+    """Bit-for-bit: the model loop is the embedding followed by cqil_group_forward per group."""
+    dtype, vocab, max_seq = torch.bfloat16, 257, 32
+    sizes = [1, 3, 2]
+    model, groups, kv_len, *_ = _tiny_model(dtype, sizes, vocab, max_seq, seed=17)
+    tokens = torch.randint(0, vocab, (1, 6), generator=synth.generator(1)).to(torch.int32).cuda()
+    ws = torch.empty(cq.cqil_model_workspace_bytes(model, 1, 6), dtype=torch.uint8, device="cuda")
+    hid = torch.empty(1, 6, TINY.d_model, dtype=dtype, device="cuda")
+    cq.cqil_model_forward(model, tokens, 1, 6, 1, False, hid, None, None, ws)
+    k_model = [g.k.clone() for g in groups]
+    emb = model._keep[4]
+    x = emb[tokens[0].long()].reshape(1, 6, -1).contiguous()
+    for g in groups:
+        g.k.zero_(); g.v.zero_(); g.set_kv_len([0])
+        x = g.forward(x, 1, advance=False)
+    torch.cuda.synchronize()
+    assert torch.equal(x, hid)
+    for g, k in zip(groups, k_model):
+        assert torch.equal(g.k, k)
