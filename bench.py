@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the CQIL hot path on one MI355X.
+
+Workload (the one the headline metric is quoted on): ONE LLaMA-33B-shaped group of P=4 input-aligned layers,
+bf16, batch 1, single-token decode steps with the KV cache growing from 512 to 640 tokens (the decode phase of
+the full-model configuration), bypass distance 1.  A "step" is one whole group step: all five kernels.
+
+Prints one JSON line: the step latency (the metric), the achieved fraction of the HBM roofline for the dominant
+kernel measured live with HIP events, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def kernel_bytes(shape, P, S, es=2):
+    """Algorithmic HBM bytes of each decode kernel for one token: every packed weight byte once, every valid
+    KV byte once, activations once (S = cached tokens before the step)."""
+    dm, f = shape.d_model, shape.d_ffn
+    return {
+        "qkv_rope": P * 3 * dm * dm * es + dm * es + P * dm * es + P * dm * 4 + 2 * P * dm * es,
+        "attn_decode": 2 * P * (S + 1) * dm * es + 2 * P * dm * 4,
+        "oproj": P * dm * dm * es + 2 * P * dm * 4,
+        "gateup": 2 * P * f * dm * es + dm * es + P * dm * 4 + P * dm * es + P * f * 4,
+        "down": P * dm * f * es + P * f * 4,
+        "merge": 2 * dm * es + P * dm * 4,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--shape", default="33b", choices=["7b", "13b", "33b"])
+    ap.add_argument("--P", type=int, default=4)
+    ap.add_argument("--bypass", type=int, default=1)
+    ap.add_argument("--kv-start", type=int, default=512)
+    ap.add_argument("--kv-span", type=int, default=128)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sequential", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2404_06709_amd import binding as cq
+    from paper_2404_06709_amd import runtime as rt
+    from paper_2404_06709_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    cq.lib()  # fails loudly if libcqil.so has not been built
+    dev = "cuda"
+    shape = synth.SHAPES[args.shape]
+    P, d_byp = args.P, args.bypass
+    dtype = torch.bfloat16
+    max_seq = args.kv_start + args.kv_span + 8
+    dims = cq.make_dims(shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, max_seq, dtype)
+
+    # synthetic inputs: weights N(0, 0.02), gains 1, KV fill and hidden state N(0, 1), all from seed 1005
+    layers = synth.make_layers(P, shape, dtype, seed=1005, device=dev)
+    group = rt.Group(dims, layers, b_max=1, device=dev)
+    gen = synth.generator(2005, dev)
+    S0 = args.kv_start
+    group.k[:, :, :, :S0] = synth.normal((P, 1, shape.n_heads, S0, shape.head_dim), 1.0, dtype, gen)
+    group.v[:, :, :, :S0] = synth.normal((P, 1, shape.n_heads, S0, shape.head_dim), 1.0, dtype, gen)
+    x = synth.normal((1, 1, shape.d_model), 1.0, dtype, gen)
+    y = torch.empty_like(x)
+    ws = group.workspace(1, 1)
+    torch.cuda.synchronize()
+
+    def run(n):
+        # the cache grows by one token per step and wraps every kv_span steps
+        for i in range(n):
+            if i % args.kv_span == 0:
+                group.set_kv_len([S0])
+            cq.cqil_group_forward(dims, P, d_byp, group.packed, group.kv, x, y, 1, 1, True, ws)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    us_step = dt / args.steps * 1e6
+
+    # per-kernel durations, HIP events on the launch stream, at the mean cache length
+    S_mean = S0 + args.kv_span // 2
+    group.set_kv_len([S_mean])
+    prof_n = 64
+    acc = np.zeros(6)
+    for i in range(prof_n + 8):
+        ms = cq.cqil_decode_step_profile(dims, P, d_byp, group.packed, group.kv, x, y, ws)
+        if i >= 8:
+            acc += np.array(ms)
+    k_us = acc / prof_n * 1e3
+    kb = kernel_bytes(shape, P, S_mean)
+    names = cq.DECODE_KERNELS
+    per_kernel = {n: {"us": round(float(k_us[i]), 2), "bytes": int(kb[n]),
+                      "gbps": round(kb[n] / (k_us[i] * 1e-6) / 1e9, 1)} for i, n in enumerate(names)}
+    dom = max(names, key=lambda n: kb[n])
+    di = names.index(dom)
+    achieved = kb[dom] / (k_us[di] * 1e-6) / 1e9
+    step_bytes = sum(kb.values())
+
+    out = {
+        "metric": "decode_us_per_token_per_P_layer_group",
+        "value": round(us_step, 2),
+        "unit": "us/token",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(us_step / 1e3, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"llama{args.shape}_shape_group_P{P}_decode_B1_kv{S0}-{S0 + args.kv_span}",
+                   "d_model": shape.d_model, "n_heads": shape.n_heads, "d_ffn": shape.d_ffn, "P": P,
+                   "bypass_d": d_byp, "batch": 1, "kv_len": [S0, S0 + args.kv_span]},
+        "tokens_per_s": round(1e6 / us_step, 1),
+        "step_hbm": {"bytes": int(step_bytes), "gbps": round(step_bytes / (us_step * 1e-6) / 1e9, 1),
+                     "frac": round(step_bytes / (us_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None},
+        "kernels": per_kernel,
+    }
+
+    if not args.no_sequential:
+        # the same four layers as four groups of one (Eq.1 chain): grouped versus sequential latency
+        seq = [rt.Group(dims, [L], b_max=1, device=dev) for L in layers]
+        for g in seq:
+            g.k[:, :, :, :S0] = group.k[:1, :, :, :S0]
+            g.v[:, :, :, :S0] = group.v[:1, :, :, :S0]
+        ws1 = seq[0].workspace(1, 1)
+        xa, xb = x.clone(), torch.empty_like(x)
+
+        def run_seq(n):
+            for i in range(n):
+                if i % args.kv_span == 0:
+                    for g in seq:
+                        g.set_kv_len([S0])
+                a, b = xa, xb
+                for g in seq:
+                    cq.cqil_group_forward(dims, 1, 0, g.packed, g.kv, a, b, 1, 1, True, ws1)
+                    a, b = b, a
+
+        nseq = max(args.steps // 4, 32)
+        run_seq(16)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_seq(nseq)
+        torch.cuda.synchronize()
+        us_seq = (time.perf_counter() - t0) / nseq * 1e6
+        out["sequential_us_per_token_same_layers"] = round(us_seq, 2)
+        out["grouped_over_sequential"] = round(us_step / us_seq, 4)
+        del seq
+
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        od = orc.Dims(shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, max_seq, 10000.0, 1e-6, orc.BF16)
+        np_layers = [synth.layer_to_numpy(L) for L in layers]
+        okc, ovc = orc.new_cache(P, 1, od), orc.new_cache(P, 1, od)
+        okc[:, :, :, :S0] = synth.widen(group.k[:, :, :, :S0])
+        ovc[:, :, :, :S0] = synth.widen(group.v[:, :, :, :S0])
+        xin = synth.widen(x)
+        orc.group_forward(od, np_layers, d_byp, okc, ovc, [S0], xin)          # untimed first touch
+        t0 = time.perf_counter()
+        for i in range(args.cpu_steps):
+            orc.group_forward(od, np_layers, d_byp, okc, ovc, [S0 + 1 + i], xin)
+        cpu_us = (time.perf_counter() - t0) / args.cpu_steps * 1e6
+        out["cpu_baseline"] = {"value": round(cpu_us, 1), "unit": "us/token", "cores": orc.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"{args.cpu_steps} decode steps of the same group (same weights, kv {S0}+)"}
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,4 +1,4 @@
-// Decode step of one CQIL group for a single new token (B*T == 1): five bandwidth-bound kernels.
+// Decode step of one CQIL group for a single new token (B*T == 1): five bandwidth-bound kernels and a merge.
 //
 //   1 qkv_rope   shared-input projection of all P layers (Eq.2's xW^Q, xW^K, xW^V applied to the one x_G of
 //                Eq.3), fused with the attention RMSNorm (one statistic for the whole group, P gains), the
@@ -7,7 +7,8 @@
 //   3 oproj      per-layer Concat(heads)W^O
 //   4 gateup     forms the P feed-forward inputs h_i = x + a_i + bypass window (Eq.4), their RMSNorm, the
 //                gate/up projections and SwiGLU
-//   5 down       one contraction over the K-concatenated Wdown: sum_i FFN_i, plus x + sum_i a_i (Eq.3/Eq.4)
+//   5 down       one contraction over the K-concatenated Wdown: sum_i FFN_i, split along K
+//   6 merge      x_out = x + sum_i a_i + sum of the K slices (Eq.3 / Eq.4)
 //
 // Every projection is a matrix-vector product streamed once from HBM: a wave owns four rows at a time, each
 // lane reads 16 contiguous bytes of each row per step, the input vector sits in LDS as fp32.
@@ -24,8 +25,7 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     const T* __restrict__ x, const T* __restrict__ wqkv, const T* __restrict__ g_attn, const float2* __restrict__ rope,
     const int32_t* __restrict__ kv_len, T* __restrict__ kc, T* __restrict__ vc, float* __restrict__ q_out,
-    int32_t* __restrict__ counters, int n_counters, int d_model, int n_heads, int d_k, int max_seq, int b_max,
-    float eps) {
+    int d_model, int n_heads, int d_k, int max_seq, int b_max, float eps) {
     extern __shared__ float smem[];
     constexpr int V = elem<T>::kVec;
     float* xs = smem;                        // xs_words(d_model)
@@ -36,9 +36,6 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     const int h = unit % n_heads;
     const int lm = unit / n_heads;  // l*3 + m
     const int l = lm / 3, m = lm % 3;
-
-    if (unit == 0)
-        for (int i = tid; i < n_counters; i += kThreads) counters[i] = 0;
 
     // one statistic for the whole group: all P layers normalise the same x (Eq.3)
     float ss = 0.f;
@@ -88,35 +85,34 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// 2. Decode attention over P independent caches, split along the cache length.
-//    grid = (P*B*n_heads, n_chunks).  Each workgroup reduces kAttnChunk slots to (max, sum, context); the
-//    last workgroup of a (layer, sequence, head) to arrive merges the chunks in chunk order.
+// 2. Decode attention over P independent caches.  One workgroup of 16 waves per (layer, sequence, head): every
+//    wave walks the cache in strides, four slot steps (K and V loads of all four in flight) per iteration, with a
+//    running maximum / sum / context (online softmax); the 16 partial results are merged through LDS.
 //    LPS = lanes that share one cache slot = head_dim * sizeof(T) / 16.
 // ---------------------------------------------------------------------------------------------------------
+constexpr int kAttnThreads = 1024;
+constexpr int kAttnWaves = kAttnThreads / kWave;
+
 template <typename T, int LPS>
-__global__ __launch_bounds__(kThreads) void attn_decode_kernel(
+__global__ __launch_bounds__(kAttnThreads) void attn_decode_kernel(
     const float* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc,
-    const int32_t* __restrict__ kv_len, float* __restrict__ part, int32_t* __restrict__ counters,
-    float* __restrict__ ctx, int B, int n_heads, int max_seq, int b_max, int n_chunks) {
+    const int32_t* __restrict__ kv_len, float* __restrict__ ctx, int B, int n_heads, int max_seq, int b_max) {
     constexpr int V = elem<T>::kVec;
     constexpr int DK = LPS * V;
-    constexpr int SPW = kWave / LPS;                      // slots per wave step
-    constexpr int NI = kAttnChunk / kWaves / SPW;         // steps per wave
-    __shared__ float red[2 * kWaves];
-    __shared__ float accs[kWaves][DK];
-    __shared__ int s_last;
+    constexpr int SPW = kWave / LPS;  // slots per wave step
+    constexpr int U = 4;              // steps per iteration
+    __shared__ float red_m[kAttnWaves], red_l[kAttnWaves];
+    __shared__ float accs[kAttnWaves][DK];
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int sub = lane % LPS, sg = lane / LPS;
-    const int unit = blockIdx.x, chunk = blockIdx.y;
+    const int unit = blockIdx.x;
     const int h = unit % n_heads;
     const int lb = unit / n_heads;
     const int b = lb % B, l = lb / B;
     int S = kv_len[b] + 1;  // slots to attend, including the token appended by the previous kernel
     if (S > max_seq) S = max_seq;
     if (S < 1) return;
-    const int n_valid = (S + kAttnChunk - 1) / kAttnChunk;
-    if (chunk >= n_valid) return;
 
     const size_t d_model = (size_t)n_heads * DK;
     const float scale = 1.0f / sqrtf((float)DK);
@@ -127,111 +123,91 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(
         for (int j = 0; j < V; ++j) qv[j] = qp[j] * scale;
     }
     const size_t head_off = (((size_t)l * b_max + b) * n_heads + h) * (size_t)max_seq * DK;
-    const T* kb = kc + head_off;
-    const T* vb = vc + head_off;
-    const int s0 = chunk * kAttnChunk + w * (kAttnChunk / kWaves) + sg;
+    const T* kb = kc + head_off + sub * V;
+    const T* vb = vc + head_off + sub * V;
 
-    float sc[NI];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int s = s0 + i * SPW;
-        float dot = 0.f;
-        if (s < S) {
-            float f[V];
-            elem<T>::unpack(load16(kb + (size_t)s * DK + sub * V), f);
-#pragma unroll
-            for (int j = 0; j < V; ++j) dot = fmaf(f[j], qv[j], dot);
-        }
-#pragma unroll
-        for (int off = LPS / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, kWave);
-        sc[i] = (s < S) ? dot : -INFINITY;
-        mx = fmaxf(mx, sc[i]);
-    }
-    mx = wave_max(mx);
-    if (lane == 0) red[w] = mx;
-    __syncthreads();
-    mx = red[0];
-#pragma unroll
-    for (int i = 1; i < kWaves; ++i) mx = fmaxf(mx, red[i]);  // finite: slot chunk*kAttnChunk < S
-
-    float acc[V];
+    float mx = -INFINITY, lsum = 0.f, acc[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) acc[j] = 0.f;
-    float lsum = 0.f;
+    const int n_steps = (S + SPW - 1) / SPW;
+    for (int i0 = w * U; i0 < n_steps; i0 += kAttnWaves * U) {
+        uint4 kraw[U], vraw[U];
+        bool ok[U];
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int s = s0 + i * SPW;
-        if (s < S) {
-            const float p = expf(sc[i] - mx);
-            lsum += p;
-            float f[V];
-            elem<T>::unpack(load16(vb + (size_t)s * DK + sub * V), f);
+        for (int u = 0; u < U; ++u) {
+            const int s = (i0 + u) * SPW + sg;
+            ok[u] = s < S;
+            kraw[u] = ok[u] ? load16(kb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
+        }
 #pragma unroll
-            for (int j = 0; j < V; ++j) acc[j] = fmaf(p, f[j], acc[j]);
+        for (int u = 0; u < U; ++u) {
+            const int s = (i0 + u) * SPW + sg;
+            vraw[u] = ok[u] ? load16(vb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
+        }
+        float sc[U], mloc = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float f[V], dot = 0.f;
+            elem<T>::unpack(kraw[u], f);
+#pragma unroll
+            for (int j = 0; j < V; ++j) dot = fmaf(f[j], qv[j], dot);
+#pragma unroll
+            for (int off = LPS / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, kWave);
+            sc[u] = ok[u] ? dot : -INFINITY;
+            mloc = fmaxf(mloc, sc[u]);
+        }
+        const float nm = fmaxf(mx, mloc);
+        if (nm > -INFINITY) {
+            const float corr = expf(mx - nm);  // exp(-inf) = 0 the first time
+            lsum *= corr;
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[j] *= corr;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float p = ok[u] ? expf(sc[u] - nm) : 0.f;
+                float f[V];
+                elem<T>::unpack(vraw[u], f);
+                lsum += p;
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[j] = fmaf(p, f[j], acc[j]);
+            }
+            mx = nm;
         }
     }
-    // combine the SPW slot groups of the wave
+    // merge the slot groups of the wave, then the waves
+    float wm = mx;
+#pragma unroll
+    for (int off = LPS; off < kWave; off <<= 1) wm = fmaxf(wm, __shfl_xor(wm, off, kWave));
+    const float sc0 = (mx == -INFINITY) ? 0.f : expf(mx - wm);
+    lsum *= sc0;
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] *= sc0;
 #pragma unroll
     for (int off = LPS; off < kWave; off <<= 1) {
         lsum += __shfl_xor(lsum, off, kWave);
 #pragma unroll
         for (int j = 0; j < V; ++j) acc[j] += __shfl_xor(acc[j], off, kWave);
     }
+    if (lane == 0) { red_m[w] = wm; red_l[w] = lsum; }
     if (sg == 0) {
 #pragma unroll
         for (int j = 0; j < V; ++j) accs[w][sub * V + j] = acc[j];
     }
-    if (lane == 0) red[kWaves + w] = lsum;
     __syncthreads();
-    float ltot = 0.f;
-#pragma unroll
-    for (int i = 0; i < kWaves; ++i) ltot += red[kWaves + i];
-
-    float* ctx_out = ctx + ((size_t)l * B + b) * d_model + (size_t)h * DK;
-    if (n_valid == 1) {
-        if (tid < DK) {
-            float c = 0.f;
-#pragma unroll
-            for (int i = 0; i < kWaves; ++i) c += accs[i][tid];
-            ctx_out[tid] = c / ltot;
-        }
-        return;
-    }
-    float* mypart = part + ((size_t)unit * n_chunks + chunk) * (DK + 2);
     if (tid < DK) {
-        float c = 0.f;
+        float gm = red_m[0];
 #pragma unroll
-        for (int i = 0; i < kWaves; ++i) c += accs[i][tid];
-        mypart[2 + tid] = c;
-    }
-    if (tid == 0) { mypart[0] = mx; mypart[1] = ltot; }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int ticket = __hip_atomic_fetch_add(&counters[unit], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (ticket == n_valid - 1);
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    if (tid < DK) {
-        const float* up = part + (size_t)unit * n_chunks * (DK + 2);
-        float M = -INFINITY;
-        for (int c = 0; c < n_valid; ++c)
-            M = fmaxf(M, __hip_atomic_load(up + (size_t)c * (DK + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        float Lsum = 0.f, cacc = 0.f;
-        for (int c = 0; c < n_valid; ++c) {
-            const float* pc = up + (size_t)c * (DK + 2);
-            const float e = expf(__hip_atomic_load(pc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - M);
-            Lsum += e * __hip_atomic_load(pc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            cacc += e * __hip_atomic_load(pc + 2 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int i = 1; i < kAttnWaves; ++i) gm = fmaxf(gm, red_m[i]);
+        float Ls = 0.f, c = 0.f;
+#pragma unroll
+        for (int i = 0; i < kAttnWaves; ++i) {
+            const float e = (red_m[i] == -INFINITY) ? 0.f : expf(red_m[i] - gm);
+            Ls += e * red_l[i];
+            c += e * accs[i][tid];
         }
-        ctx_out[tid] = cacc / Lsum;
+        ctx[((size_t)l * B + b) * d_model + (size_t)h * DK + tid] = c / Ls;
     }
-    if (tid == 0) counters[unit] = 0;
 }
-
 // ---------------------------------------------------------------------------------------------------------
 // 3. Output projection, per layer: a_l = Wo_l ctx_l.  grid = (row blocks, P).  Wo is K-concatenated:
 //    packed row o holds the P layers' rows side by side, layer l's segment starts at l*d_model.
@@ -308,23 +284,20 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// 5. Down projection over the K-concatenated Wdown [d_model][P*d_ffn] with the merge of Eq.3 / Eq.4:
-//    x_out = x + sum_i a_i + Wdown_cat u_cat.   grid = (row blocks, K slices).  With more than one slice the
-//    last workgroup of a row block to arrive adds the slices in slice order (deterministic).
+// 5. Down projection over the K-concatenated Wdown [d_model][P*d_ffn]: the sum over the group's layers in
+//    Eq.3 / Eq.4 is part of the dot product.  grid = (row blocks, K slices); every slice writes its partial
+//    sums, the merge kernel below adds them in slice order (deterministic, no atomics).
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(kThreads) void down_kernel(const T* __restrict__ x, const float* __restrict__ a,
-                                                         const float* __restrict__ u, const T* __restrict__ wdown,
-                                                         float* __restrict__ part, int32_t* __restrict__ counters,
-                                                         T* __restrict__ x_out, int32_t* __restrict__ kv_len, int advance,
-                                                         int P, int d_model, int d_ffn, int rows_per_wg, int slice_len) {
+__global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict__ u, const T* __restrict__ wdown,
+                                                         float* __restrict__ part, int P, int d_model, int d_ffn,
+                                                         int rows_per_wg, int slice_len) {
     extern __shared__ float smem[];
     constexpr int V = elem<T>::kVec;
-    __shared__ int s_last;
     float* xs = smem;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int K = P * d_ffn;
-    const int slice = blockIdx.y, n_slices = gridDim.y;
+    const int slice = blockIdx.y;
     const int k0 = slice * slice_len;
     const int len = min(slice_len, K - k0);
     for (int k = tid; k < len; k += kThreads) xs[xs_index<V>(k)] = u[k0 + k];
@@ -338,30 +311,22 @@ __global__ __launch_bounds__(kThreads) void down_kernel(const T* __restrict__ x,
         dot4<T>(r, r + K, r + 2 * (size_t)K, r + 3 * (size_t)K, xs, len, s);
         if (lane == 0) *reinterpret_cast<float4*>(mypart + o) = make_float4(s[0], s[1], s[2], s[3]);
     }
-    if (advance && blockIdx.x == 0 && slice == 0 && tid == 0) kv_len[0] += 1;
+}
 
-    if (n_slices > 1) {
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) {
-            const int ticket =
-                __hip_atomic_fetch_add(&counters[blockIdx.x], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (ticket == n_slices - 1);
-        }
-        __syncthreads();
-        if (!s_last) return;
-        __threadfence();
-    } else {
-        __syncthreads();
-    }
-    for (int o = row0 + tid; o < row1; o += kThreads) {
+// 6. Merge of Eq.3 / Eq.4: x_out = x + sum_i a_i + sum_slices partial; also advances the cache length.
+template <typename T>
+__global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ x, const float* __restrict__ a,
+                                                    const float* __restrict__ part, T* __restrict__ x_out,
+                                                    int32_t* __restrict__ kv_len, int advance, int P, int n_slices,
+                                                    int d_model) {
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    if (o < d_model) {
         float v = elem<T>::load(x + o);
         for (int j = 0; j < P; ++j) v += a[(size_t)j * d_model + o];
-        for (int s = 0; s < n_slices; ++s)
-            v += __hip_atomic_load(part + (size_t)s * d_model + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int s = 0; s < n_slices; ++s) v += part[(size_t)s * d_model + o];
         elem<T>::store(x_out + o, v);
     }
-    if (n_slices > 1 && tid == 0) counters[blockIdx.x] = 0;
+    if (advance && o == 0) kv_len[0] += 1;
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -376,33 +341,26 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     const T* g_attn = (const T*)(s.packed + s.pl.g_attn);
     const T* g_ffn = (const T*)(s.packed + s.pl.g_ffn);
     const float2* rope = (const float2*)(s.packed + s.pl.rope);
-    int32_t* counters = (int32_t*)(s.ws + s.wl.counters);
     float* q = (float*)(s.ws + s.wl.q);
     float* ctx = (float*)(s.ws + s.wl.ctx);
-    float* apart = (float*)(s.ws + s.wl.attn_part);
     float* a = (float*)(s.ws + s.wl.a);
     float* u = (float*)(s.ws + s.wl.u);
     float* dpart = (float*)(s.ws + s.wl.down_part);
     const int bd = s.bypass_d >= P ? P - 1 : s.bypass_d;
     const int xw = (dm + 511) & ~511;
-
-    // counters: [0, P*n_heads) attention units, then the down projection's row blocks
     const int rows_o = 32, rows_d = 32, j_per = 32;
-    const int n_att = P * nh;
-    const int nrb_d = (dm + rows_d - 1) / rows_d;
 
+    // optional per-kernel timing: event i is recorded before kernel i, the last event after the last kernel
+#define CQIL_MARK(i) do { if (s.ev) (void)hipEventRecord(s.ev[i], st); } while (0)
+    CQIL_MARK(0);
     hipLaunchKernelGGL(HIP_KERNEL_NAME(qkv_rope_kernel<T>), dim3(P * 3 * nh), dim3(kThreads),
                        (xw + dk + 16) * sizeof(float), st, (const T*)s.x_in, wqkv, g_attn, rope, s.kv_len, (T*)s.kc,
-                       (T*)s.vc, q, counters, s.wl.n_counters, dm, nh, dk, d.max_seq, s.b_max, d.rms_eps);
-
-    int n_chunks = (s.max_kv_len + 1 + kAttnChunk - 1) / kAttnChunk;
-    if (n_chunks > s.wl.n_chunks) n_chunks = s.wl.n_chunks;
-    if (n_chunks < 1) n_chunks = 1;
+                       (T*)s.vc, q, dm, nh, dk, d.max_seq, s.b_max, d.rms_eps);
+    CQIL_MARK(1);
     const int lps = dk * (int)sizeof(T) / 16;
-    dim3 ga(n_att, n_chunks);
-#define CQIL_ATTN(LPS)                                                                                              \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_decode_kernel<T, LPS>), ga, dim3(kThreads), 0, st, q, (const T*)s.kc,   \
-                       (const T*)s.vc, s.kv_len, apart, counters, ctx, 1, nh, d.max_seq, s.b_max, s.wl.n_chunks)
+#define CQIL_ATTN(LPS)                                                                                               \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_decode_kernel<T, LPS>), dim3(P * nh), dim3(kAttnThreads), 0, st, q,      \
+                       (const T*)s.kc, (const T*)s.vc, s.kv_len, ctx, 1, nh, d.max_seq, s.b_max)
     switch (lps) {
         case 4: CQIL_ATTN(4); break;
         case 8: CQIL_ATTN(8); break;
@@ -411,17 +369,22 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
         default: return hipErrorInvalidValue;
     }
 #undef CQIL_ATTN
-
+    CQIL_MARK(2);
     hipLaunchKernelGGL(HIP_KERNEL_NAME(oproj_kernel<T>), dim3((dm + rows_o - 1) / rows_o, P), dim3(kThreads),
                        xw * sizeof(float), st, ctx, wo, a, P, dm, rows_o);
-
+    CQIL_MARK(3);
     hipLaunchKernelGGL(HIP_KERNEL_NAME(gateup_kernel<T>), dim3((f + j_per - 1) / j_per, P), dim3(kThreads),
                        (xw + 16) * sizeof(float), st, (const T*)s.x_in, a, wgu, g_ffn, u, P, bd, dm, f, j_per,
                        d.rms_eps);
-
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(down_kernel<T>), dim3(nrb_d, s.wl.n_slices), dim3(kThreads),
-                       ((s.wl.down_slice + 511) & ~511) * sizeof(float), st, (const T*)s.x_in, a, u, wdown, dpart,
-                       counters + n_att, (T*)s.x_out, s.kv_len, s.advance, P, dm, f, rows_d, s.wl.down_slice);
+    CQIL_MARK(4);
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(down_kernel<T>), dim3((dm + rows_d - 1) / rows_d, s.wl.n_slices),
+                       dim3(kThreads), ((s.wl.down_slice + 511) & ~511) * sizeof(float), st, u, wdown, dpart, P, dm, f,
+                       rows_d, s.wl.down_slice);
+    CQIL_MARK(5);
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 255) / 256), dim3(256), 0, st, (const T*)s.x_in, a,
+                       dpart, (T*)s.x_out, s.kv_len, s.advance, P, s.wl.n_slices, dm);
+    CQIL_MARK(6);
+#undef CQIL_MARK
     return hipGetLastError();
 }
 

@@ -47,7 +47,6 @@ int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* W) {
     if ((long long)B * T > (1ll << 24)) return CQIL_EINVAL;
     const size_t M = (size_t)B * T, dm = d->d_model, f = d->d_ffn, es = esize(d->dtype);
     memset(W, 0, sizeof(*W));
-    W->n_chunks = (d->max_seq + kAttnChunk - 1) / kAttnChunk;
     const size_t K = (size_t)P * f;
     // K slices of the decode down projection: equal lengths, multiples of 512, at most kDownSliceMax
     int ns = (int)((K + kDownSliceMax - 1) / kDownSliceMax);
@@ -55,12 +54,9 @@ int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* W) {
     ns = (int)((K + sl - 1) / sl);
     W->n_slices = ns;
     W->down_slice = (int)sl;
-    W->n_counters = P * B * d->n_heads + (int)((dm + 31) / 32) + 64;
     size_t off = 0;
-    W->counters = off;  off = align_up(off + (size_t)W->n_counters * sizeof(int32_t));
     W->q = off;         off = align_up(off + (size_t)P * M * dm * sizeof(float));
     W->ctx = off;       off = align_up(off + (size_t)P * M * dm * sizeof(float));
-    W->attn_part = off; off = align_up(off + (size_t)P * B * d->n_heads * W->n_chunks * (d->head_dim + 2) * sizeof(float));
     W->a = off;         off = align_up(off + (size_t)P * M * dm * sizeof(float));
     if (M == 1) {
         W->u = off;         off = align_up(off + K * sizeof(float));
@@ -154,8 +150,10 @@ int cqil_pack_group(const cqil_dims* dims, int P, const cqil_layer* layers, void
 
 static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const void* packed, void* kc, void* vc,
                               int32_t* kv_len, int b_max, int max_kv_len, const void* x_in, void* x_out, int B, int T,
-                              int advance, void* workspace, size_t workspace_bytes, hipStream_t st) {
+                              int advance, void* workspace, size_t workspace_bytes, hipStream_t st,
+                              hipEvent_t* ev = nullptr) {
     StepArgs a;
+    a.ev = ev;
     int rc = packed_layout(dims, P, &a.pl);
     if (rc) return rc;
     if (bypass_d < 0 || B < 1 || T < 1) return CQIL_EINVAL;
@@ -184,6 +182,24 @@ int cqil_group_forward(const cqil_dims* dims, int P, int bypass_d, const void* p
     int rc = group_forward_impl(dims, P, bypass_d, packed, kv->k, kv->v, kv->kv_len, kv->b_max, kv->max_kv_len, x_in,
                                 x_out, B, T, advance_kv_len, workspace, workspace_bytes, (hipStream_t)stream);
     if (rc == CQIL_OK && advance_kv_len) kv->max_kv_len += T;
+    return rc;
+}
+
+int cqil_decode_step_profile(const cqil_dims* dims, int P, int bypass_d, const void* packed, cqil_kv* kv,
+                             const void* x_in, void* x_out, void* workspace, size_t workspace_bytes, void* stream,
+                             float* kernel_ms_out) {
+    if (!kv || !kernel_ms_out) return CQIL_EINVAL;
+    hipEvent_t ev[7];
+    for (int i = 0; i < 7; ++i)
+        if (hipEventCreate(&ev[i]) != hipSuccess) return CQIL_EHIP;
+    int rc = group_forward_impl(dims, P, bypass_d, packed, kv->k, kv->v, kv->kv_len, kv->b_max, kv->max_kv_len, x_in,
+                                x_out, 1, 1, 0, workspace, workspace_bytes, (hipStream_t)stream, ev);
+    if (rc == CQIL_OK) {
+        if (hipEventSynchronize(ev[6]) != hipSuccess) rc = CQIL_EHIP;
+        for (int i = 0; i < 6 && rc == CQIL_OK; ++i)
+            if (hipEventElapsedTime(&kernel_ms_out[i], ev[i], ev[i + 1]) != hipSuccess) rc = CQIL_EHIP;
+    }
+    for (int i = 0; i < 7; ++i) (void)hipEventDestroy(ev[i]);
     return rc;
 }
 

@@ -13,17 +13,14 @@ inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a
 inline size_t esize(int dtype) { return dtype == CQIL_BF16 ? 2 : 4; }
 
 constexpr int kGuBlock = 16;        // gate/up rows are interleaved in blocks of this many rows
-constexpr int kAttnChunk = 128;     // KV slots per workgroup of the split-KV decode attention
 constexpr int kDownSliceMax = 8192; // longest K slice of the decode down projection (fp32 words of LDS)
 constexpr int kMaxP = 16;
 
 // Workspace of one group step.  Offsets in bytes, all multiples of 256.
 struct WsLayout {
     // decode fast path (B*T == 1) and shared
-    size_t counters;   // int32 [n_counters]      arrival counters (zeroed by the first kernel of a step)
     size_t q;          // f32 [P][M][d_model]     rotated queries
     size_t ctx;        // f32 [P][M][d_model]     attention context (heads concatenated)
-    size_t attn_part;  // f32 [P*B*n_heads][n_chunks][head_dim+2]  split-KV partials (max, sum, context)
     size_t a;          // f32 [P][M][d_model]     attention outputs a_i
     size_t u;          // f32 [M][P*d_ffn]        SwiGLU outputs (decode path)
     size_t down_part;  // f32 [n_slices][d_model] split-K partials of the down projection
@@ -35,7 +32,7 @@ struct WsLayout {
     size_t gu;         // act [M][P*2*d_ffn]
     size_t u_act;      // act [M][P*d_ffn]
     size_t total;
-    int n_counters, n_chunks, n_slices, down_slice;
+    int n_slices, down_slice;
 };
 
 int check_dims(const cqil_dims* d, int P);
@@ -61,6 +58,7 @@ struct StepArgs {
     void* x_out;
     char* ws;
     WsLayout wl;
+    hipEvent_t* ev;  // null, or 7 events recorded around the six decode kernels
 };
 
 hipError_t launch_decode_step(const StepArgs& a, hipStream_t st);   // B*T == 1
