@@ -22,6 +22,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
+# what the same counters read for a plain copy kernel (profiles/decode_step_33b_P4_B1_hbm_traffic.md).  Only valid
+# for the workload it was measured on; other workloads report null.
+MEASURED_TRAFFIC = {("33b", 4, "gateup"): 1_909_988_841}
+
 
 def kernel_bytes(shape, P, S, es=2):
     """Algorithmic HBM bytes of each decode kernel for one token: every packed weight byte once, every valid
@@ -139,7 +144,8 @@ def main() -> int:
         "step_hbm": {"bytes": int(step_bytes), "gbps": round(step_bytes / (us_step * 1e-6) / 1e9, 1),
                      "frac": round(step_bytes / (us_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None},
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC.get((args.shape, P, dom))},
         "kernels": per_kernel,
     }
 
