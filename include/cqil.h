@@ -159,6 +159,15 @@ int cqil_model_forward(cqil_model *m /* host */, const int32_t *tokens, int B, i
                        int advance_kv_len, void *hidden_out, float *logits_out, int32_t *next_token_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* Launch-shape knobs of the single-token decode kernels (process-wide, host-only, not thread-safe; set them
+ * before sizing workspaces).  Keys: "rows_o", "rows_d" (weight rows per workgroup of the O / down projection,
+ * multiples of 16; rows_o = 0 picks by shape), "j_per" (gate/up row pairs per workgroup, multiple of 8; 0 picks
+ * by shape), "down_slice_max" (longest K slice of the down projection, multiple of 512, at most 12288),
+ * "qkv_parts" (workgroups per head in the QKV kernel: 1, 2 or 4), "pipeline" (0..3: variants of the streaming
+ * inner loop; 0 is the default).  Results do not depend on rows_o, rows_d, j_per, qkv_parts or pipeline; the number of
+ * K slices changes the summation order of the down projection.  Unknown key or bad value: CQIL_EINVAL. */
+int cqil_set_tuning(const char *key, int value);
+
 /* Library build information (host-only). */
 const char *cqil_version(void);
 

@@ -82,6 +82,7 @@ def lib() -> C.CDLL:
         L.cqil_decode_step_profile.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_void_p, C.POINTER(cqil_kv),
                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
                                                C.POINTER(C.c_float)]
+        L.cqil_set_tuning.argtypes = [C.c_char_p, C.c_int]
         L.cqil_model_workspace_bytes.restype = C.c_size_t
         L.cqil_model_workspace_bytes.argtypes = [C.POINTER(cqil_model), C.c_int, C.c_int]
         L.cqil_model_forward.argtypes = [C.POINTER(cqil_model), C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -176,6 +177,12 @@ def cqil_group_forward(dims: cqil_dims, P: int, bypass_d: int, packed: torch.Ten
                                   workspace.numel() * workspace.element_size(), _stream())
     if rc:
         raise CqilError(rc, "cqil_group_forward")
+
+
+def cqil_set_tuning(key: str, value: int) -> None:
+    rc = lib().cqil_set_tuning(key.encode(), int(value))
+    if rc:
+        raise CqilError(rc, f"cqil_set_tuning({key}, {value})")
 
 
 DECODE_KERNELS = ("qkv_rope", "attn_decode", "oproj", "gateup", "down", "merge")

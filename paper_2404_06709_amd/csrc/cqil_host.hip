@@ -6,6 +6,8 @@
 
 namespace cqil {
 
+Tuning g_tune;
+
 static bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 int check_dims(const cqil_dims* d, int P) {
@@ -48,8 +50,9 @@ int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* W) {
     const size_t M = (size_t)B * T, dm = d->d_model, f = d->d_ffn, es = esize(d->dtype);
     memset(W, 0, sizeof(*W));
     const size_t K = (size_t)P * f;
-    // K slices of the decode down projection: equal lengths, multiples of 512, at most kDownSliceMax
-    int ns = (int)((K + kDownSliceMax - 1) / kDownSliceMax);
+    // K slices of the decode down projection: equal lengths, multiples of 512, at most the tuned maximum
+    const size_t smax = (size_t)g_tune.down_slice_max;
+    int ns = (int)((K + smax - 1) / smax);
     size_t sl = ((K + ns - 1) / ns + 511) / 512 * 512;
     ns = (int)((K + sl - 1) / sl);
     W->n_slices = ns;
@@ -92,6 +95,30 @@ const char* cqil_strerror(int status) {
         case CQIL_EHIP: return "HIP launch failure";
         default: return "unknown status";
     }
+}
+
+int cqil_set_tuning(const char* key, int value) {
+    if (!key) return CQIL_EINVAL;
+    if (!strcmp(key, "rows_o") || !strcmp(key, "rows_d")) {
+        const bool is_o = key[5] == 'o';
+        if (!(is_o && value == 0) && (value < 16 || value > 4096 || value % 16)) return CQIL_EINVAL;
+        (is_o ? g_tune.rows_o : g_tune.rows_d) = value;
+    } else if (!strcmp(key, "j_per")) {
+        if (value != 0 && (value < 8 || value > 4096 || value % 8)) return CQIL_EINVAL;
+        g_tune.j_per = value;
+    } else if (!strcmp(key, "down_slice_max")) {
+        if (value < 512 || value > 12288 || value % 512) return CQIL_EINVAL;
+        g_tune.down_slice_max = value;
+    } else if (!strcmp(key, "qkv_parts")) {
+        if (value != 1 && value != 2 && value != 4) return CQIL_EINVAL;
+        g_tune.qkv_parts = value;
+    } else if (!strcmp(key, "pipeline")) {
+        if (value < 0 || value > 3) return CQIL_EINVAL;
+        g_tune.pipeline = value;
+    } else {
+        return CQIL_EINVAL;
+    }
+    return CQIL_OK;
 }
 
 int cqil_packed_layout_of(const cqil_dims* dims, int P, cqil_packed_layout* out) { return packed_layout(dims, P, out); }

@@ -13,8 +13,16 @@ inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a
 inline size_t esize(int dtype) { return dtype == CQIL_BF16 ? 2 : 4; }
 
 constexpr int kGuBlock = 16;        // gate/up rows are interleaved in blocks of this many rows
-constexpr int kDownSliceMax = 8192; // longest K slice of the decode down projection (fp32 words of LDS)
 constexpr int kMaxP = 16;
+
+// Launch-shape knobs of the decode kernels (cqil_set_tuning).  rows_o / rows_d: weight rows per workgroup of the
+// O and down projections (multiples of 16); j_per: gate/up row pairs per workgroup (multiple of 8);
+// down_slice_max: longest K slice of the down projection (multiple of 512, at most 12288); pipeline: 1 = loads
+// of the next tile are issued before the current one is consumed.
+struct Tuning {
+    int rows_o = 0, rows_d = 32, j_per = 0, down_slice_max = 6144, pipeline = 0, qkv_parts = 2;  // 0 = by shape
+};
+extern Tuning g_tune;
 
 // Workspace of one group step.  Offsets in bytes, all multiples of 256.
 struct WsLayout {
