@@ -28,17 +28,18 @@ HBM_PEAK_GBPS = 8000.0
 MEASURED_TRAFFIC = {("33b", 4, "gateup"): 1_909_988_841}
 
 
-def kernel_bytes(shape, P, S, es=2):
-    """Algorithmic HBM bytes of each decode kernel for one token: every packed weight byte once, every valid
-    KV byte once, activations once (S = cached tokens before the step)."""
-    dm, f = shape.d_model, shape.d_ffn
+def kernel_bytes(shape, P, lens, es=2):
+    """Algorithmic HBM bytes of each decode kernel for one step of B = len(lens) sequences: every packed weight
+    byte once, every valid KV byte once, activations once (lens = cached tokens per sequence before the step)."""
+    dm, f, B = shape.d_model, shape.d_ffn, len(lens)
+    ues = 4 if B == 1 else 2   # SwiGLU outputs: fp32 for one token, bf16 for a small batch
     return {
-        "qkv_rope": P * 3 * dm * dm * es + dm * es + P * dm * es + P * dm * 4 + 2 * P * dm * es,
-        "attn_decode": 2 * P * (S + 1) * dm * es + 2 * P * dm * 4,
-        "oproj": P * dm * dm * es + 2 * P * dm * 4,
-        "gateup": 2 * P * f * dm * es + dm * es + P * dm * 4 + P * dm * es + P * f * 4,
-        "down": P * dm * f * es + P * f * 4,
-        "merge": 2 * dm * es + P * dm * 4,
+        "qkv_rope": P * 3 * dm * dm * es + B * dm * es + P * dm * es + B * P * dm * 4 + 2 * B * P * dm * es,
+        "attn_decode": sum(2 * P * (S + 1) * dm * es for S in lens) + 2 * B * P * dm * 4,
+        "oproj": P * dm * dm * es + 2 * B * P * dm * 4,
+        "gateup": 2 * P * f * dm * es + B * dm * es + B * P * dm * 4 + P * dm * es + B * P * f * ues,
+        "down": P * dm * f * es + B * P * f * ues,
+        "merge": 2 * B * dm * es + B * P * dm * 4,
     }
 
 
@@ -52,6 +53,8 @@ def main() -> int:
     ap.add_argument("--bypass", type=int, default=1)
     ap.add_argument("--kv-start", type=int, default=512)
     ap.add_argument("--kv-span", type=int, default=128)
+    ap.add_argument("--batch", type=int, default=1, help="sequences per step (bf16 small-batch path for 2..8)")
+    ap.add_argument("--kv-hi", type=int, default=0, help="with --batch: lengths uniform in [kv-start, kv-hi]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=4)
@@ -75,27 +78,33 @@ def main() -> int:
     shape = synth.SHAPES[args.shape]
     P, d_byp = args.P, args.bypass
     dtype = torch.bfloat16
-    max_seq = args.kv_start + args.kv_span + 8
+    B = args.batch
+    if B > 1:
+        lens0 = [int(v) for v in synth.kv_lengths(B, args.kv_start, max(args.kv_hi, args.kv_start), seed=1003)]
+    else:
+        lens0 = [args.kv_start]
+    max_seq = max(lens0) + args.kv_span + 8
     dims = cq.make_dims(shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, max_seq, dtype)
 
     # synthetic inputs: weights N(0, 0.02), gains 1, KV fill and hidden state N(0, 1), all from seed 1005
     layers = synth.make_layers(P, shape, dtype, seed=1005, device=dev)
-    group = rt.Group(dims, layers, b_max=1, device=dev)
+    group = rt.Group(dims, layers, b_max=B, device=dev)
     gen = synth.generator(2005, dev)
     S0 = args.kv_start
-    group.k[:, :, :, :S0] = synth.normal((P, 1, shape.n_heads, S0, shape.head_dim), 1.0, dtype, gen)
-    group.v[:, :, :, :S0] = synth.normal((P, 1, shape.n_heads, S0, shape.head_dim), 1.0, dtype, gen)
-    x = synth.normal((1, 1, shape.d_model), 1.0, dtype, gen)
+    Smax = max(lens0)
+    group.k[:, :, :, :Smax] = synth.normal((P, B, shape.n_heads, Smax, shape.head_dim), 1.0, dtype, gen)
+    group.v[:, :, :, :Smax] = synth.normal((P, B, shape.n_heads, Smax, shape.head_dim), 1.0, dtype, gen)
+    x = synth.normal((B, 1, shape.d_model), 1.0, dtype, gen)
     y = torch.empty_like(x)
-    ws = group.workspace(1, 1)
+    ws = group.workspace(B, 1)
     torch.cuda.synchronize()
 
     def run(n):
         # the cache grows by one token per step and wraps every kv_span steps
         for i in range(n):
             if i % args.kv_span == 0:
-                group.set_kv_len([S0])
-            cq.cqil_group_forward(dims, P, d_byp, group.packed, group.kv, x, y, 1, 1, True, ws)
+                group.set_kv_len(lens0)
+            cq.cqil_group_forward(dims, P, d_byp, group.packed, group.kv, x, y, B, 1, True, ws)
 
     run(args.warmup)
     torch.cuda.synchronize()
@@ -106,16 +115,16 @@ def main() -> int:
     us_step = dt / args.steps * 1e6
 
     # per-kernel durations, HIP events on the launch stream, at the mean cache length
-    S_mean = S0 + args.kv_span // 2
-    group.set_kv_len([S_mean])
+    lens_mean = [S + args.kv_span // 2 for S in lens0]
+    group.set_kv_len(lens_mean)
     prof_n = 64
     acc = np.zeros(6)
     for i in range(prof_n + 8):
-        ms = cq.cqil_decode_step_profile(dims, P, d_byp, group.packed, group.kv, x, y, ws)
+        ms = cq.cqil_decode_step_profile(dims, P, d_byp, group.packed, group.kv, x, y, ws, B)
         if i >= 8:
             acc += np.array(ms)
     k_us = acc / prof_n * 1e3
-    kb = kernel_bytes(shape, P, S_mean)
+    kb = kernel_bytes(shape, P, lens_mean)
     names = cq.DECODE_KERNELS
     per_kernel = {n: {"us": round(float(k_us[i]), 2), "bytes": int(kb[n]),
                       "gbps": round(kb[n] / (k_us[i] * 1e-6) / 1e9, 1)} for i, n in enumerate(names)}
@@ -126,7 +135,7 @@ def main() -> int:
 
     out = {
         "metric": "decode_us_per_token_per_P_layer_group",
-        "value": round(us_step, 2),
+        "value": round(us_step / B, 2),
         "unit": "us/token",
         "n_gpus": 1,
         "steps": args.steps,
@@ -137,19 +146,19 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"llama{args.shape}_shape_group_P{P}_decode_B1_kv{S0}-{S0 + args.kv_span}",
+        "config": {"workload": f"llama{args.shape}_shape_group_P{P}_decode_B{B}_kv{min(lens0)}-{max(lens0) + args.kv_span}",
                    "d_model": shape.d_model, "n_heads": shape.n_heads, "d_ffn": shape.d_ffn, "P": P,
-                   "bypass_d": d_byp, "batch": 1, "kv_len": [S0, S0 + args.kv_span]},
-        "tokens_per_s": round(1e6 / us_step, 1),
+                   "bypass_d": d_byp, "batch": B, "kv_len_start": lens0, "kv_span": args.kv_span},
+        "tokens_per_s": round(B * 1e6 / us_step, 1),
         "step_hbm": {"bytes": int(step_bytes), "gbps": round(step_bytes / (us_step * 1e-6) / 1e9, 1),
                      "frac": round(step_bytes / (us_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC.get((args.shape, P, dom))},
+                     "traffic": MEASURED_TRAFFIC.get((args.shape, P, dom)) if B == 1 else None},
         "kernels": per_kernel,
     }
 
-    if not args.no_sequential:
+    if not args.no_sequential and B == 1:
         # the same four layers as four groups of one (Eq.1 chain): grouped versus sequential latency
         seq = [rt.Group(dims, [L], b_max=1, device=dev) for L in layers]
         for g in seq:
@@ -179,7 +188,7 @@ def main() -> int:
         out["grouped_over_sequential"] = round(us_step / us_seq, 4)
         del seq
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and B == 1:
         import oracle as orc
         od = orc.Dims(shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, max_seq, 10000.0, 1e-6, orc.BF16)
         np_layers = [synth.layer_to_numpy(L) for L in layers]

@@ -80,7 +80,7 @@ def lib() -> C.CDLL:
                                          C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
         L.cqil_decode_step_profile.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_void_p, C.POINTER(cqil_kv),
-                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
+                                               C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p,
                                                C.POINTER(C.c_float)]
         L.cqil_set_tuning.argtypes = [C.c_char_p, C.c_int]
         L.cqil_model_workspace_bytes.restype = C.c_size_t
@@ -189,11 +189,12 @@ DECODE_KERNELS = ("qkv_rope", "attn_decode", "oproj", "gateup", "down", "merge")
 
 
 def cqil_decode_step_profile(dims: cqil_dims, P: int, bypass_d: int, packed: torch.Tensor, kv: cqil_kv,
-                             x_in: torch.Tensor, x_out: torch.Tensor, workspace: torch.Tensor) -> List[float]:
-    """Per-kernel milliseconds of one single-token decode step, in DECODE_KERNELS order."""
+                             x_in: torch.Tensor, x_out: torch.Tensor, workspace: torch.Tensor,
+                             B: int = 1) -> List[float]:
+    """Per-kernel milliseconds of one decode step (one new token for each of B sequences), in DECODE_KERNELS order."""
     ms = (C.c_float * 6)()
     rc = lib().cqil_decode_step_profile(C.byref(dims), P, bypass_d, _ptr(packed), C.byref(kv), _ptr(x_in), _ptr(x_out),
-                                        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(), ms)
+                                        B, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(), ms)
     if rc:
         raise CqilError(rc, "cqil_decode_step_profile")
     return [float(v) for v in ms]

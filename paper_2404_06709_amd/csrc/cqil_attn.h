@@ -1,0 +1,154 @@
+// Kernels shared by the single-token and the small-batch decode paths: attention over the per-layer caches
+// and the final merge.
+#pragma once
+#include "cqil_dev.h"
+
+namespace cqil {
+
+// Attention (Eq.2: softmax(QK^T/sqrt(d_k))V) of one query per workgroup over P independent caches.  One workgroup
+// of 16 waves per (layer, token, head): every wave walks the cache in strides, four slot steps (K and V loads of
+// all four in flight) per iteration, with a running maximum / sum / context (online softmax); the 16 partial
+// results are merged through LDS.  q, ctx: fp32 [P][M][d_model].
+// LPS = lanes that share one cache slot = head_dim * sizeof(T) / 16.
+constexpr int kAttnThreads = 1024;
+constexpr int kAttnWaves = kAttnThreads / kWave;
+
+template <typename T, int LPS>
+__global__ __launch_bounds__(kAttnThreads) void attn_decode_kernel(
+    const float* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc,
+    const int32_t* __restrict__ kv_len, float* __restrict__ ctx, int M, int T_new, int n_heads, int max_seq, int b_max) {
+    constexpr int V = elem<T>::kVec;
+    constexpr int DK = LPS * V;
+    constexpr int SPW = kWave / LPS;  // slots per wave step
+    constexpr int U = 4;              // steps per iteration
+    __shared__ float red_m[kAttnWaves], red_l[kAttnWaves];
+    __shared__ float accs[kAttnWaves][DK];
+
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int sub = lane % LPS, sg = lane / LPS;
+    const int unit = blockIdx.x;
+    const int h = unit % n_heads;
+    const int lm = unit / n_heads;
+    const int m = lm % M, l = lm / M;      // token row m = b * T_new + t
+    const int b = m / T_new, t = m % T_new;
+    int S = kv_len[b] + t + 1;  // slots to attend: the cache, and the new tokens up to and including this one
+    if (S > max_seq) S = max_seq;
+    if (S < 1) return;
+
+    const size_t d_model = (size_t)n_heads * DK;
+    const float scale = 1.0f / sqrtf((float)DK);
+    float qv[V];
+    {
+        const float* qp = q + ((size_t)l * M + m) * d_model + (size_t)h * DK + sub * V;
+#pragma unroll
+        for (int j = 0; j < V; ++j) qv[j] = qp[j] * scale;
+    }
+    const size_t head_off = (((size_t)l * b_max + b) * n_heads + h) * (size_t)max_seq * DK;
+    const T* kb = kc + head_off + sub * V;
+    const T* vb = vc + head_off + sub * V;
+
+    float mx = -INFINITY, lsum = 0.f, acc[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] = 0.f;
+    const int n_steps = (S + SPW - 1) / SPW;
+    for (int i0 = w * U; i0 < n_steps; i0 += kAttnWaves * U) {
+        uint4 kraw[U], vraw[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = (i0 + u) * SPW + sg;
+            ok[u] = s < S;
+            kraw[u] = ok[u] ? load16(kb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = (i0 + u) * SPW + sg;
+            vraw[u] = ok[u] ? load16(vb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
+        }
+        float sc[U], mloc = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float f[V], dot = 0.f;
+            elem<T>::unpack(kraw[u], f);
+#pragma unroll
+            for (int j = 0; j < V; ++j) dot = fmaf(f[j], qv[j], dot);
+#pragma unroll
+            for (int off = LPS / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, kWave);
+            sc[u] = ok[u] ? dot : -INFINITY;
+            mloc = fmaxf(mloc, sc[u]);
+        }
+        const float nm = fmaxf(mx, mloc);
+        if (nm > -INFINITY) {
+            const float corr = expf(mx - nm);  // exp(-inf) = 0 the first time
+            lsum *= corr;
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[j] *= corr;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float p = ok[u] ? expf(sc[u] - nm) : 0.f;
+                float f[V];
+                elem<T>::unpack(vraw[u], f);
+                lsum += p;
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[j] = fmaf(p, f[j], acc[j]);
+            }
+            mx = nm;
+        }
+    }
+    // merge the slot groups of the wave, then the waves
+    float wm = mx;
+#pragma unroll
+    for (int off = LPS; off < kWave; off <<= 1) wm = fmaxf(wm, __shfl_xor(wm, off, kWave));
+    const float sc0 = (mx == -INFINITY) ? 0.f : expf(mx - wm);
+    lsum *= sc0;
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] *= sc0;
+#pragma unroll
+    for (int off = LPS; off < kWave; off <<= 1) {
+        lsum += __shfl_xor(lsum, off, kWave);
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] += __shfl_xor(acc[j], off, kWave);
+    }
+    if (lane == 0) { red_m[w] = wm; red_l[w] = lsum; }
+    if (sg == 0) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) accs[w][sub * V + j] = acc[j];
+    }
+    __syncthreads();
+    if (tid < DK) {
+        float gm = red_m[0];
+#pragma unroll
+        for (int i = 1; i < kAttnWaves; ++i) gm = fmaxf(gm, red_m[i]);
+        float Ls = 0.f, c = 0.f;
+#pragma unroll
+        for (int i = 0; i < kAttnWaves; ++i) {
+            const float e = (red_m[i] == -INFINITY) ? 0.f : expf(red_m[i] - gm);
+            Ls += e * red_l[i];
+            c += e * accs[i][tid];
+        }
+        ctx[((size_t)l * M + m) * d_model + (size_t)h * DK + tid] = c / Ls;
+    }
+}
+
+// Merge of Eq.3 / Eq.4 for M token rows: x_out = x + sum_i a_i + sum of the K-slice partials of the down
+// projection, added in slice order; also advances the cache lengths.  grid = (ceil(d_model/256), M).
+//   a [P][M][d_model] fp32, part [n_slices][M][d_model] fp32
+template <typename T>
+__global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ x, const float* __restrict__ a,
+                                                    const float* __restrict__ part, T* __restrict__ x_out,
+                                                    int32_t* __restrict__ kv_len, int advance, int P, int n_slices,
+                                                    int M, int d_model, int B, int T_new) {
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    const int m = blockIdx.y;
+    if (o < d_model) {
+        const size_t idx = (size_t)m * d_model + o;
+        float v = elem<T>::load(x + idx);
+        for (int j = 0; j < P; ++j) v += a[(size_t)j * M * d_model + idx];
+        for (int s = 0; s < n_slices; ++s) v += part[(size_t)s * M * d_model + idx];
+        elem<T>::store(x_out + idx, v);
+    }
+    if (advance && m == 0 && blockIdx.x == 0)
+        for (int b = threadIdx.x; b < B; b += 256) kv_len[b] += T_new;
+}
+
+}  // namespace cqil

@@ -13,6 +13,7 @@
 // Every projection is a matrix-vector product streamed once from HBM: a wave owns four rows at a time, each
 // lane reads 16 contiguous bytes of each row per step, the input vector sits in LDS as fp32.
 #include "cqil_dev.h"
+#include "cqil_attn.h"
 #include "cqil_gemv.h"
 #include "cqil_internal.h"
 
@@ -99,124 +100,8 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
 //    running maximum / sum / context (online softmax); the 16 partial results are merged through LDS.
 //    LPS = lanes that share one cache slot = head_dim * sizeof(T) / 16.
 // ---------------------------------------------------------------------------------------------------------
-constexpr int kAttnThreads = 1024;
-constexpr int kAttnWaves = kAttnThreads / kWave;
+// (kernel in cqil_attn.h)
 
-template <typename T, int LPS>
-__global__ __launch_bounds__(kAttnThreads) void attn_decode_kernel(
-    const float* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc,
-    const int32_t* __restrict__ kv_len, float* __restrict__ ctx, int B, int n_heads, int max_seq, int b_max) {
-    constexpr int V = elem<T>::kVec;
-    constexpr int DK = LPS * V;
-    constexpr int SPW = kWave / LPS;  // slots per wave step
-    constexpr int U = 4;              // steps per iteration
-    __shared__ float red_m[kAttnWaves], red_l[kAttnWaves];
-    __shared__ float accs[kAttnWaves][DK];
-
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-    const int sub = lane % LPS, sg = lane / LPS;
-    const int unit = blockIdx.x;
-    const int h = unit % n_heads;
-    const int lb = unit / n_heads;
-    const int b = lb % B, l = lb / B;
-    int S = kv_len[b] + 1;  // slots to attend, including the token appended by the previous kernel
-    if (S > max_seq) S = max_seq;
-    if (S < 1) return;
-
-    const size_t d_model = (size_t)n_heads * DK;
-    const float scale = 1.0f / sqrtf((float)DK);
-    float qv[V];
-    {
-        const float* qp = q + ((size_t)l * B + b) * d_model + (size_t)h * DK + sub * V;
-#pragma unroll
-        for (int j = 0; j < V; ++j) qv[j] = qp[j] * scale;
-    }
-    const size_t head_off = (((size_t)l * b_max + b) * n_heads + h) * (size_t)max_seq * DK;
-    const T* kb = kc + head_off + sub * V;
-    const T* vb = vc + head_off + sub * V;
-
-    float mx = -INFINITY, lsum = 0.f, acc[V];
-#pragma unroll
-    for (int j = 0; j < V; ++j) acc[j] = 0.f;
-    const int n_steps = (S + SPW - 1) / SPW;
-    for (int i0 = w * U; i0 < n_steps; i0 += kAttnWaves * U) {
-        uint4 kraw[U], vraw[U];
-        bool ok[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int s = (i0 + u) * SPW + sg;
-            ok[u] = s < S;
-            kraw[u] = ok[u] ? load16(kb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int s = (i0 + u) * SPW + sg;
-            vraw[u] = ok[u] ? load16(vb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
-        }
-        float sc[U], mloc = -INFINITY;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float f[V], dot = 0.f;
-            elem<T>::unpack(kraw[u], f);
-#pragma unroll
-            for (int j = 0; j < V; ++j) dot = fmaf(f[j], qv[j], dot);
-#pragma unroll
-            for (int off = LPS / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, kWave);
-            sc[u] = ok[u] ? dot : -INFINITY;
-            mloc = fmaxf(mloc, sc[u]);
-        }
-        const float nm = fmaxf(mx, mloc);
-        if (nm > -INFINITY) {
-            const float corr = expf(mx - nm);  // exp(-inf) = 0 the first time
-            lsum *= corr;
-#pragma unroll
-            for (int j = 0; j < V; ++j) acc[j] *= corr;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const float p = ok[u] ? expf(sc[u] - nm) : 0.f;
-                float f[V];
-                elem<T>::unpack(vraw[u], f);
-                lsum += p;
-#pragma unroll
-                for (int j = 0; j < V; ++j) acc[j] = fmaf(p, f[j], acc[j]);
-            }
-            mx = nm;
-        }
-    }
-    // merge the slot groups of the wave, then the waves
-    float wm = mx;
-#pragma unroll
-    for (int off = LPS; off < kWave; off <<= 1) wm = fmaxf(wm, __shfl_xor(wm, off, kWave));
-    const float sc0 = (mx == -INFINITY) ? 0.f : expf(mx - wm);
-    lsum *= sc0;
-#pragma unroll
-    for (int j = 0; j < V; ++j) acc[j] *= sc0;
-#pragma unroll
-    for (int off = LPS; off < kWave; off <<= 1) {
-        lsum += __shfl_xor(lsum, off, kWave);
-#pragma unroll
-        for (int j = 0; j < V; ++j) acc[j] += __shfl_xor(acc[j], off, kWave);
-    }
-    if (lane == 0) { red_m[w] = wm; red_l[w] = lsum; }
-    if (sg == 0) {
-#pragma unroll
-        for (int j = 0; j < V; ++j) accs[w][sub * V + j] = acc[j];
-    }
-    __syncthreads();
-    if (tid < DK) {
-        float gm = red_m[0];
-#pragma unroll
-        for (int i = 1; i < kAttnWaves; ++i) gm = fmaxf(gm, red_m[i]);
-        float Ls = 0.f, c = 0.f;
-#pragma unroll
-        for (int i = 0; i < kAttnWaves; ++i) {
-            const float e = (red_m[i] == -INFINITY) ? 0.f : expf(red_m[i] - gm);
-            Ls += e * red_l[i];
-            c += e * accs[i][tid];
-        }
-        ctx[((size_t)l * B + b) * d_model + (size_t)h * DK + tid] = c / Ls;
-    }
-}
 // ---------------------------------------------------------------------------------------------------------
 // 3. Output projection, per layer: a_l = Wo_l ctx_l.  grid = (row blocks, P).  Wo is K-concatenated:
 //    packed row o holds the P layers' rows side by side, layer l's segment starts at l*d_model.
@@ -331,21 +216,7 @@ __global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict_
         });
 }
 
-// 6. Merge of Eq.3 / Eq.4: x_out = x + sum_i a_i + sum_slices partial; also advances the cache length.
-template <typename T>
-__global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ x, const float* __restrict__ a,
-                                                    const float* __restrict__ part, T* __restrict__ x_out,
-                                                    int32_t* __restrict__ kv_len, int advance, int P, int n_slices,
-                                                    int d_model) {
-    const int o = blockIdx.x * 256 + threadIdx.x;
-    if (o < d_model) {
-        float v = elem<T>::load(x + o);
-        for (int j = 0; j < P; ++j) v += a[(size_t)j * d_model + o];
-        for (int s = 0; s < n_slices; ++s) v += part[(size_t)s * d_model + o];
-        elem<T>::store(x_out + o, v);
-    }
-    if (advance && o == 0) kv_len[0] += 1;
-}
+// 6. Merge of Eq.3 / Eq.4: merge_kernel in cqil_attn.h
 
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
@@ -392,7 +263,7 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     const int lps = dk * (int)sizeof(T) / 16;
 #define CQIL_ATTN(LPS)                                                                                               \
     hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_decode_kernel<T, LPS>), dim3(P * nh), dim3(kAttnThreads), 0, st, q,      \
-                       (const T*)s.kc, (const T*)s.vc, s.kv_len, ctx, 1, nh, d.max_seq, s.b_max)
+                       (const T*)s.kc, (const T*)s.vc, s.kv_len, ctx, 1, 1, nh, d.max_seq, s.b_max)
     switch (lps) {
         case 4: CQIL_ATTN(4); break;
         case 8: CQIL_ATTN(8); break;
@@ -422,8 +293,8 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     switch (pipe) { case 1: CQIL_DOWN(1); break; case 2: CQIL_DOWN(2); break; case 3: CQIL_DOWN(3); break; default: CQIL_DOWN(0); }
 #undef CQIL_DOWN
     CQIL_MARK(5);
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 255) / 256), dim3(256), 0, st, (const T*)s.x_in, a,
-                       dpart, (T*)s.x_out, s.kv_len, s.advance, P, s.wl.n_slices, dm);
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 255) / 256, 1), dim3(256), 0, st, (const T*)s.x_in,
+                       a, dpart, (T*)s.x_out, s.kv_len, s.advance, P, s.wl.n_slices, 1, dm, 1, 1);
     CQIL_MARK(6);
 #undef CQIL_MARK
     return hipGetLastError();

@@ -136,6 +136,19 @@ def test_token_parallel_path_matches_oracle(shape, dtype):
     pair.step(pair.hidden(1, 67, seed=3), 0, label=f"long chunk {dtype}")  # more than one 64-row tile, ragged
 
 
+@pytest.mark.parametrize("shape,P", [(MID, 1), (MID, 4), (synth.Shape(256, 4, 64, 2752), 2), (synth.Shape(1024, 8, 128, 2816), 3)])
+def test_small_batch_matrix_core_path_matches_oracle(shape, P):
+    """bf16, 2..8 token rows per call: the decode kernels that feed the matrix cores."""
+    pair = Pair(shape, P, torch.bfloat16, max_seq=300, b_max=8, seed=900 + P, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([0, 3, 127, 128, 200, 64, 1, 250], seed=6)
+    pair.step(pair.hidden(8, 1, seed=1), 1, label="batch 8")
+    pair.step(pair.hidden(2, 1, seed=2), 0, label="batch 2")
+    pair.step(pair.hidden(3, 1, seed=3), P - 1, label="batch 3")
+    pair.step(pair.hidden(2, 3, seed=4), 1, label="2 sequences x 3 new tokens")
+    pair.step(pair.hidden(1, 8, seed=5), 2, label="8-token chunk")
+    pair.step(pair.hidden(5, 1, seed=6), 1, label="batch 5")
+
+
 def test_prefill_then_decode_equals_one_prefill():
     """Property that holds at any size: prefilling T tokens equals prefilling T-1 and decoding one."""
     pair = Pair(TINY, 2, torch.float32, max_seq=64, b_max=1, seed=11, w_std=0.05, gain_jitter=0.1)
