@@ -45,8 +45,8 @@ typedef enum {
 
 typedef enum { CQIL_F32 = 0, CQIL_BF16 = 1 } cqil_dtype;
 
-/* Shape of one decoder layer.  Requirements: n_heads * head_dim == d_model; head_dim even and a
- * multiple of 8, at most 256; d_model % 8 == 0; d_ffn % 16 == 0; max_seq >= 1. */
+/* Shape of one decoder layer.  Requirements: n_heads * head_dim == d_model; head_dim a power of two,
+ * 32..256 (bf16) or 32..128 (fp32); d_model % 32 == 0, at most 14336; d_ffn % 16 == 0; max_seq >= 1. */
 typedef struct {
     int d_model, n_heads, head_dim, d_ffn, max_seq;
     float rope_base, rms_eps;
@@ -74,15 +74,23 @@ typedef struct {
                         past max_seq even if this bound is wrong).  Advanced with kv_len. */
 } cqil_kv;
 
-/* Byte offsets of the parts of a packed group (all multiples of 256).
- *   wqkv   [P][3][d_model][d_model]      rows of Wq, Wk, Wv of layer 0, then layer 1, ... (N-concat)
- *   wo     [d_model][P][d_model]         row o = the P layers' rows o of Wo side by side (K-concat)
- *   wgu    [P][d_ffn/16][2][16][d_model] 16 rows of Wgate, then the matching 16 rows of Wup (N-concat)
- *   wdown  [d_model][P][d_ffn]           row o = the P layers' rows o of Wdown side by side (K-concat)
+/* Byte offsets of the parts of a packed group (all multiples of 256).  Logical matrices:
+ *   wqkv   [P*3*d_model][d_model]   rows of Wq, Wk, Wv of layer 0, then of layer 1, ...        (N-concat)
+ *   wo     [d_model][P*d_model]     row o = the P layers' rows o of Wo side by side             (K-concat)
+ *   wgu    [P*2*d_ffn][d_model]     per layer: 16 rows of Wgate, the matching 16 rows of Wup,
+ *                                   the next 16 rows of Wgate, ...                              (N-concat)
+ *   wdown  [d_model][P*d_ffn]       row o = the P layers' rows o of Wdown side by side          (K-concat)
+ * With the K-concatenated layouts the sums over layers in Eq.3 / Eq.4 are part of the contraction.
+ * Each logical matrix W[R][K] is stored in 1 KiB tiles of 16 rows x KB columns, KB = 64 / sizeof(element)
+ * (32 for bf16, 16 for fp32); K is padded with zero columns to a multiple of KB (Kp).  The tiles of one 16-row
+ * strip follow each other along k; inside a tile the 16-byte pieces are ordered [g][i], piece (g, i) holding
+ * columns KB*kb + (KB/4)*g .. + KB/4 - 1 of row 16*rt + i.  Element (r, k) therefore sits at element offset
+ *   ((r/16)*(Kp/KB) + k/KB)*16*KB + ((k%KB)/(KB/4))*16*(KB/4) + (r%16)*(KB/4) + k%(KB/4).
+ * A 64-lane wave reads one tile with one contiguous 16-byte load per lane, and lane i + 16 g receives its
+ * fragment (row i, k group g) of the A operand of the 16x16x32 bf16 matrix-core instruction.
  *   g_attn, g_ffn [P][d_model]
  *   rope   [max_seq][head_dim/2] pairs (cos, sin) of pos * rope_base^(-2i/head_dim), fp32,
- *          evaluated in double and rounded once
- * With the K-concatenated layouts the sums over layers in Eq.3 / Eq.4 are part of the contraction. */
+ *          evaluated in double and rounded once */
 typedef struct {
     size_t wqkv, wo, wgu, wdown, g_attn, g_ffn, rope, total;
 } cqil_packed_layout;
@@ -160,12 +168,10 @@ int cqil_model_forward(cqil_model *m /* host */, const int32_t *tokens, int B, i
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /* Launch-shape knobs of the single-token decode kernels (process-wide, host-only, not thread-safe; set them
- * before sizing workspaces).  Keys: "rows_o", "rows_d" (weight rows per workgroup of the O / down projection,
- * multiples of 16; rows_o = 0 picks by shape), "j_per" (gate/up row pairs per workgroup, multiple of 8; 0 picks
- * by shape), "down_slice_max" (longest K slice of the down projection, multiple of 512, at most 12288),
- * "qkv_parts" (workgroups per head in the QKV kernel: 1, 2 or 4), "pipeline" (0..3: variants of the streaming
- * inner loop; 0 is the default).  Results do not depend on rows_o, rows_d, j_per, qkv_parts or pipeline; the number of
- * K slices changes the summation order of the down projection.  Unknown key or bad value: CQIL_EINVAL. */
+ * before sizing workspaces).  Keys: "ksplit_qkv", "ksplit_o", "ksplit_gu" (waves that share one unit of work and
+ * split its k range: 1, 2, 4 or 8), "down_slice_max" (longest K slice of the down projection, multiple of 512, at
+ * most 12288).  The k split and the number of K slices change the order in which partial sums are added, nothing
+ * else.  Unknown key or bad value: CQIL_EINVAL. */
 int cqil_set_tuning(const char *key, int value);
 
 /* Library build information (host-only). */

@@ -3,40 +3,62 @@
 //   1 qkv_rope   shared-input projection of all P layers (Eq.2's xW^Q, xW^K, xW^V applied to the one x_G of
 //                Eq.3), fused with the attention RMSNorm (one statistic for the whole group, P gains), the
 //                rotary embedding and the KV-cache append
-//   2 attn       softmax(QK^T/sqrt(d_k))V over the P independent caches, split along the cache length
+//   2 attn       softmax(QK^T/sqrt(d_k))V over the P independent caches (cqil_attn.h)
 //   3 oproj      per-layer Concat(heads)W^O
 //   4 gateup     forms the P feed-forward inputs h_i = x + a_i + bypass window (Eq.4), their RMSNorm, the
 //                gate/up projections and SwiGLU
 //   5 down       one contraction over the K-concatenated Wdown: sum_i FFN_i, split along K
 //   6 merge      x_out = x + sum_i a_i + sum of the K slices (Eq.3 / Eq.4)
 //
-// Every projection is a matrix-vector product streamed once from HBM: a wave owns four rows at a time, each
-// lane reads 16 contiguous bytes of each row per step, the input vector sits in LDS as fp32.
-#include "cqil_dev.h"
+// Every projection is a matrix-vector product streamed once from HBM in the tiled layout: a wave owns 16-row
+// strips, each of its loads reads one contiguous 1 KiB tile, the input vector sits in LDS as fp32.  A unit of
+// work is one strip (O, down) or the two strips that meet in an epilogue (the two halves of 16 rotary pairs; 16
+// gate rows and their 16 up rows).  A workgroup of 8 waves takes 8 / ksplit units; with ksplit > 1 the waves of
+// a unit split the k range and add their parts through LDS in a fixed order.
 #include "cqil_attn.h"
+#include "cqil_dev.h"
 #include "cqil_gemv.h"
 #include "cqil_internal.h"
 
 namespace cqil {
 
+constexpr int kU = 8;  // tiles in flight per wave
+
+// Combines the ksplit partial results of a unit.  Every wave of the workgroup calls this (it contains a
+// barrier when ksplit > 1); afterwards the wave with ks == 0 holds the totals in y[].
+template <int NY>
+__device__ __forceinline__ void combine_ksplit(float (&y)[NY], int ksplit, int ul, int ks, float* red) {
+    if (ksplit == 1) return;
+    const int lane = threadIdx.x & 63;
+    if (ks > 0 && lane < 16) {
+#pragma unroll
+        for (int n = 0; n < NY; ++n) red[((ul * 8 + ks) * NY + n) * 16 + lane] = y[n];
+    }
+    __syncthreads();
+    if (ks == 0 && lane < 16) {
+        for (int s = 1; s < ksplit; ++s)
+#pragma unroll
+            for (int n = 0; n < NY; ++n) y[n] += red[((ul * 8 + s) * NY + n) * 16 + lane];
+    }
+}
+constexpr int kRedFloats = 8 * 8 * 2 * 16;  // [unit in workgroup][ks][NY <= 2][16]
+
 // ---------------------------------------------------------------------------------------------------------
-// 1. RMSNorm + QKV projection + rotary embedding + KV append.  One workgroup per (layer, q|k|v, head).
+// 1. RMSNorm + QKV projection + rotary embedding + KV append.  grid = (unit blocks, P); a unit is the pair of
+//    strips holding rows (e, e + d_k/2), e = 16 tp .. 16 tp + 15, of one head of q, k or v.
 // ---------------------------------------------------------------------------------------------------------
-template <typename T, int PIPE>
+template <typename T>
 __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     const T* __restrict__ x, const T* __restrict__ wqkv, const T* __restrict__ g_attn, const float2* __restrict__ rope,
     const int32_t* __restrict__ kv_len, T* __restrict__ kc, T* __restrict__ vc, float* __restrict__ q_out,
-    int d_model, int n_heads, int d_k, int max_seq, int b_max, float eps, int parts) {
+    int d_model, int n_heads, int d_k, int max_seq, int b_max, float eps, int ksplit) {
     extern __shared__ float smem[];
-    constexpr int V = elem<T>::kVec;
-    float* xs = smem;                        // xs_words(d_model)
-    float* y = xs + xs_words(d_model);       // d_k
-    float* scratch = y + d_k;                // 16
+    constexpr int KB = tile<T>::KB, TE = tile<T>::kElems;
+    float* xs = smem;             // d_model
+    float* red = xs + d_model;    // kRedFloats
+    float* scratch = red + kRedFloats;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-    const int unit = blockIdx.x / parts, part = blockIdx.x % parts;  // a head may be split over several workgroups
-    const int h = unit % n_heads;
-    const int lm = unit / n_heads;  // l*3 + m
-    const int l = lm / 3, m = lm % 3;
+    const int l = blockIdx.y;
 
     // one statistic for the whole group: all P layers normalise the same x (Eq.3)
     float ss = 0.f;
@@ -47,104 +69,103 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     ss = block_sum(ss, scratch);
     const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
     const T* g = g_attn + (size_t)l * d_model;
-    for (int k = tid; k < d_model; k += kThreads)
-        xs[xs_index<V>(k)] = elem<T>::load(x + k) * r * elem<T>::load(g + k);
+    for (int k = tid; k < d_model; k += kThreads) xs[k] = elem<T>::load(x + k) * r * elem<T>::load(g + k);
     __syncthreads();
 
-    // rows of this head; a wave takes the two rows of a rotary pair together: (e, e + d_k/2)
     const int half = d_k >> 1;
-    const T* wbase = wqkv + ((size_t)lm * d_model + (size_t)h * d_k) * d_model;
-    const int gp = half / 2 / parts;  // groups of two rotary pairs handled by this workgroup
-    stream_rows<T, PIPE>(
-        part * gp + w, (part + 1) * gp, kWaves, d_model, xs,
-        [&](int g, const T* (&r)[4]) {
-            const int e0 = 2 * g;
-            r[0] = wbase + (size_t)e0 * d_model;
-            r[1] = wbase + (size_t)(e0 + 1) * d_model;
-            r[2] = wbase + (size_t)(e0 + half) * d_model;
-            r[3] = wbase + (size_t)(e0 + 1 + half) * d_model;
-        },
-        [&](int g, const float (&s)[4]) {
-            const int e0 = 2 * g;
-            if (lane == 0) { y[e0] = s[0]; y[e0 + 1] = s[1]; y[e0 + half] = s[2]; y[e0 + 1 + half] = s[3]; }
-        });
-    __syncthreads();
+    const int pairs_per_head = half / 16;
+    const int units = 3 * n_heads * pairs_per_head;   // per layer
+    const int uw = kWaves / ksplit;
+    const int ul = w / ksplit, ks = w % ksplit;
+    const int unit = blockIdx.x * uw + ul;
+    const bool on = unit < units;
+    const int tp = unit % pairs_per_head;
+    const int hu = unit / pairs_per_head;
+    const int h = hu % n_heads, m = hu / n_heads;  // m: 0,1,2 = q,k,v
+    const int nkb = d_model / KB;
+    const int per = (nkb + ksplit - 1) / ksplit;
+    const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
+    float y[2] = {0.f, 0.f};
+    if (on) {
+        const size_t strip_a = ((size_t)(l * 3 + m) * d_model + (size_t)h * d_k + 16 * tp) / 16;
+        const size_t strip_b = strip_a + half / 16;
+        y[0] = tile_strip_dot<T, kU>(wqkv + (strip_a * nkb + kb0) * TE, kb1 - kb0, xs + kb0 * KB);
+        y[1] = tile_strip_dot<T, kU>(wqkv + (strip_b * nkb + kb0) * TE, kb1 - kb0, xs + kb0 * KB);
+    }
+    combine_ksplit<2>(y, ksplit, ul, ks, red);
 
     const int pos = kv_len[0];
-    const int i = part * 2 * gp + tid;  // rotary pair (i, i + half)
-    if (tid < 2 * gp && pos >= 0 && pos < max_seq) {
-        const float a = y[i], b = y[i + half];
+    if (on && ks == 0 && lane < 16 && pos >= 0 && pos < max_seq) {
+        const int e = 16 * tp + lane;  // rotary pair (e, e + half)
+        const float a = y[0], b = y[1];
         if (m == 2) {
             T* dst = vc + (((size_t)l * b_max * n_heads + h) * max_seq + pos) * d_k;
-            elem<T>::store(dst + i, a);
-            elem<T>::store(dst + i + half, b);
+            elem<T>::store(dst + e, a);
+            elem<T>::store(dst + e + half, b);
         } else {
-            const float2 cs = rope[(size_t)pos * half + i];
+            const float2 cs = rope[(size_t)pos * half + e];
             const float ra = a * cs.x - b * cs.y, rb = b * cs.x + a * cs.y;
             if (m == 0) {
                 float* dst = q_out + (size_t)l * d_model + (size_t)h * d_k;
-                dst[i] = ra;
-                dst[i + half] = rb;
+                dst[e] = ra;
+                dst[e + half] = rb;
             } else {
                 T* dst = kc + (((size_t)l * b_max * n_heads + h) * max_seq + pos) * d_k;
-                elem<T>::store(dst + i, ra);
-                elem<T>::store(dst + i + half, rb);
+                elem<T>::store(dst + e, ra);
+                elem<T>::store(dst + e + half, rb);
             }
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// 2. Decode attention over P independent caches.  One workgroup of 16 waves per (layer, sequence, head): every
-//    wave walks the cache in strides, four slot steps (K and V loads of all four in flight) per iteration, with a
-//    running maximum / sum / context (online softmax); the 16 partial results are merged through LDS.
-//    LPS = lanes that share one cache slot = head_dim * sizeof(T) / 16.
+// 3. Output projection, per layer: a_l = Wo_l ctx_l.  grid = (unit blocks, P); a unit is one strip of 16 output
+//    rows.  Wo is K-concatenated: the columns of layer l are the tiles l*d_model/KB .. of every strip.
 // ---------------------------------------------------------------------------------------------------------
-// (kernel in cqil_attn.h)
-
-// ---------------------------------------------------------------------------------------------------------
-// 3. Output projection, per layer: a_l = Wo_l ctx_l.  grid = (row blocks, P).  Wo is K-concatenated:
-//    packed row o holds the P layers' rows side by side, layer l's segment starts at l*d_model.
-// ---------------------------------------------------------------------------------------------------------
-template <typename T, int PIPE>
+template <typename T>
 __global__ __launch_bounds__(kThreads) void oproj_kernel(const float* __restrict__ ctx, const T* __restrict__ wo,
-                                                          float* __restrict__ a, int P, int d_model, int rows_per_wg) {
+                                                          float* __restrict__ a, int P, int d_model, int ksplit) {
     extern __shared__ float smem[];
-    constexpr int V = elem<T>::kVec;
+    constexpr int KB = tile<T>::KB, TE = tile<T>::kElems;
     float* xs = smem;
+    float* red = xs + d_model;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int l = blockIdx.y;
     const float* c = ctx + (size_t)l * d_model;
-    for (int k = tid; k < d_model; k += kThreads) xs[xs_index<V>(k)] = c[k];
+    for (int k = tid; k < d_model; k += kThreads) xs[k] = c[k];
     __syncthreads();
-    const int row0 = blockIdx.x * rows_per_wg;
-    const int row1 = min(row0 + rows_per_wg, d_model);
-    const size_t ld = (size_t)P * d_model;
-    stream_rows<T, PIPE>(
-        w, (row1 - row0) / 4, kWaves, d_model, xs,
-        [&](int g, const T* (&r)[4]) {
-            const T* p = wo + (size_t)(row0 + 4 * g) * ld + (size_t)l * d_model;
-            r[0] = p; r[1] = p + ld; r[2] = p + 2 * ld; r[3] = p + 3 * ld;
-        },
-        [&](int g, const float (&s)[4]) {
-            if (lane == 0)
-                *reinterpret_cast<float4*>(a + (size_t)l * d_model + row0 + 4 * g) = make_float4(s[0], s[1], s[2], s[3]);
-        });
+    const int units = d_model / 16;
+    const int uw = kWaves / ksplit;
+    const int ul = w / ksplit, ks = w % ksplit;
+    const int unit = blockIdx.x * uw + ul;
+    const bool on = unit < units;
+    const int nkb = d_model / KB;               // tiles of one layer
+    const size_t strip_tiles = (size_t)P * nkb;  // tiles of a whole strip
+    const int per = (nkb + ksplit - 1) / ksplit;
+    const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
+    float y[1] = {0.f};
+    if (on)
+        y[0] = tile_strip_dot<T, kU>(wo + ((size_t)unit * strip_tiles + (size_t)l * nkb + kb0) * TE, kb1 - kb0,
+                                     xs + kb0 * KB);
+    combine_ksplit<1>(y, ksplit, ul, ks, red);
+    if (on && ks == 0 && lane < 16) a[(size_t)l * d_model + 16 * unit + lane] = y[0];
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// 4. Bypass window + FFN RMSNorm + gate/up projection + SwiGLU.  grid = (blocks of j, P).
+// 4. Bypass window + FFN RMSNorm + gate/up projection + SwiGLU.  grid = (unit blocks, P); a unit is one packed
+//    block: the strip of 16 gate rows and the strip of the matching 16 up rows.
 //    h_l = x + sum_{j = max(0, l-d)}^{l} a_j   (Eq.4: own attention plus the d preceding layers' outputs)
 // ---------------------------------------------------------------------------------------------------------
-template <typename T, int PIPE>
+template <typename T>
 __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ x, const float* __restrict__ a,
                                                            const T* __restrict__ wgu, const T* __restrict__ g_ffn,
                                                            float* __restrict__ u, int P, int bypass_d, int d_model,
-                                                           int d_ffn, int j_per_wg, float eps) {
+                                                           int d_ffn, float eps, int ksplit) {
     extern __shared__ float smem[];
-    constexpr int V = elem<T>::kVec;
+    constexpr int KB = tile<T>::KB, TE = tile<T>::kElems;
     float* xs = smem;
-    float* scratch = xs + xs_words(d_model);
+    float* red = xs + d_model;
+    float* scratch = red + kRedFloats;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int l = blockIdx.y;
     const int jlo = max(0, l - bypass_d);
@@ -152,71 +173,58 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
     for (int k = tid; k < d_model; k += kThreads) {
         float hv = elem<T>::load(x + k);
         for (int j = jlo; j <= l; ++j) hv += a[(size_t)j * d_model + k];
-        xs[xs_index<V>(k)] = hv;
+        xs[k] = hv;
         ss += hv * hv;
     }
     ss = block_sum(ss, scratch);
     const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
     const T* g = g_ffn + (size_t)l * d_model;
-    for (int k = tid; k < d_model; k += kThreads) xs[xs_index<V>(k)] *= r * elem<T>::load(g + k);
+    for (int k = tid; k < d_model; k += kThreads) xs[k] *= r * elem<T>::load(g + k);
     __syncthreads();
 
-    const int j0 = blockIdx.x * j_per_wg;
-    const int j1 = min(j0 + j_per_wg, d_ffn);
-    const T* wl = wgu + (size_t)l * 2 * d_ffn * d_model;
-    stream_rows<T, PIPE>(
-        w, (j1 - j0) / 2, kWaves, d_model, xs,
-        [&](int g, const T* (&r)[4]) {
-            // packed row of gate j: block (j/16) of 32 rows, gate rows first, then the up rows
-            const int j = j0 + 2 * g;
-            const T* rg = wl + ((size_t)(j / kGuBlock) * 2 * kGuBlock + (j % kGuBlock)) * d_model;
-            const T* ru = rg + (size_t)kGuBlock * d_model;
-            r[0] = rg; r[1] = rg + d_model; r[2] = ru; r[3] = ru + d_model;
-        },
-        [&](int g, const float (&s)[4]) {
-            if (lane == 0) {
-                const int j = j0 + 2 * g;
-                const float u0 = s[0] / (1.0f + expf(-s[0])) * s[2];
-                const float u1 = s[1] / (1.0f + expf(-s[1])) * s[3];
-                *reinterpret_cast<float2*>(u + (size_t)l * d_ffn + j) = make_float2(u0, u1);
-            }
-        });
+    const int units = d_ffn / kGuBlock;
+    const int uw = kWaves / ksplit;
+    const int ul = w / ksplit, ks = w % ksplit;
+    const int unit = blockIdx.x * uw + ul;
+    const bool on = unit < units;
+    const int nkb = d_model / KB;
+    const int per = (nkb + ksplit - 1) / ksplit;
+    const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
+    float y[2] = {0.f, 0.f};
+    if (on) {
+        const size_t strip_g = (size_t)l * 2 * d_ffn / 16 + 2 * (size_t)unit;  // gate strip; the up strip follows
+        y[0] = tile_strip_dot<T, kU>(wgu + (strip_g * nkb + kb0) * TE, kb1 - kb0, xs + kb0 * KB);
+        y[1] = tile_strip_dot<T, kU>(wgu + ((strip_g + 1) * nkb + kb0) * TE, kb1 - kb0, xs + kb0 * KB);
+    }
+    combine_ksplit<2>(y, ksplit, ul, ks, red);
+    if (on && ks == 0 && lane < 16)
+        u[(size_t)l * d_ffn + unit * kGuBlock + lane] = y[0] / (1.0f + expf(-y[0])) * y[1];
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// 5. Down projection over the K-concatenated Wdown [d_model][P*d_ffn]: the sum over the group's layers in
-//    Eq.3 / Eq.4 is part of the dot product.  grid = (row blocks, K slices); every slice writes its partial
-//    sums, the merge kernel below adds them in slice order (deterministic, no atomics).
+// 5. Down projection over the K-concatenated Wdown [d_model][P*d_ffn (+ zero padding)]: the sum over the group's
+//    layers in Eq.3 / Eq.4 is part of the dot product.  grid = (strip blocks, K slices); every slice writes its
+//    partial sums, merge_kernel adds them in slice order (deterministic, no atomics).
 // ---------------------------------------------------------------------------------------------------------
-template <typename T, int PIPE>
+template <typename T>
 __global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict__ u, const T* __restrict__ wdown,
-                                                         float* __restrict__ part, int P, int d_model, int d_ffn,
-                                                         int rows_per_wg, int slice_len) {
+                                                         float* __restrict__ part, int K, int Kp, int d_model,
+                                                         int slice_len) {
     extern __shared__ float smem[];
-    constexpr int V = elem<T>::kVec;
+    constexpr int KB = tile<T>::KB, TE = tile<T>::kElems;
     float* xs = smem;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-    const int K = P * d_ffn;
     const int slice = blockIdx.y;
     const int k0 = slice * slice_len;
-    const int len = min(slice_len, K - k0);
-    for (int k = tid; k < len; k += kThreads) xs[xs_index<V>(k)] = u[k0 + k];
+    const int len = min(slice_len, Kp - k0);  // multiple of KB
+    for (int k = tid; k < len; k += kThreads) xs[k] = (k0 + k < K) ? u[k0 + k] : 0.f;
     __syncthreads();
-    const int row0 = blockIdx.x * rows_per_wg;
-    const int row1 = min(row0 + rows_per_wg, d_model);
-    float* mypart = part + (size_t)slice * d_model;
-    stream_rows<T, PIPE>(
-        w, (row1 - row0) / 4, kWaves, len, xs,
-        [&](int g, const T* (&r)[4]) {
-            const T* p = wdown + (size_t)(row0 + 4 * g) * K + k0;
-            r[0] = p; r[1] = p + K; r[2] = p + 2 * (size_t)K; r[3] = p + 3 * (size_t)K;
-        },
-        [&](int g, const float (&s)[4]) {
-            if (lane == 0) *reinterpret_cast<float4*>(mypart + row0 + 4 * g) = make_float4(s[0], s[1], s[2], s[3]);
-        });
+    const int unit = blockIdx.x * kWaves + w;
+    if (unit >= d_model / 16) return;
+    const size_t strip_tiles = (size_t)Kp / KB;
+    const float y = tile_strip_dot<T, kU>(wdown + ((size_t)unit * strip_tiles + k0 / KB) * TE, len / KB, xs);
+    if (lane < 16) part[(size_t)slice * d_model + 16 * unit + lane] = y;
 }
-
-// 6. Merge of Eq.3 / Eq.4: merge_kernel in cqil_attn.h
 
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
@@ -236,29 +244,20 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     float* u = (float*)(s.ws + s.wl.u);
     float* dpart = (float*)(s.ws + s.wl.down_part);
     const int bd = s.bypass_d >= P ? P - 1 : s.bypass_d;
-    const int xw = (dm + 511) & ~511;
-    // launch shapes: measured on 7B/13B/33B-shaped groups; the O projection wants at least ~400 workgroups,
-    // the gate/up kernel ~0.7-1 MB of weights per workgroup
-    int rows_o = g_tune.rows_o, j_per = g_tune.j_per;
-    const int rows_d = g_tune.rows_d;
-    if (rows_o == 0) {
-        rows_o = 64;
-        while (rows_o > 16 && ((dm + rows_o - 1) / rows_o) * P < 400) rows_o >>= 1;
-    }
-    if (j_per == 0) j_per = dm <= 4096 ? 64 : 32;
-    const int pipe = g_tune.pipeline;
-    int parts = g_tune.qkv_parts;
-    while (parts > 1 && (dk / 4) % parts) parts >>= 1;  // whole groups of two rotary pairs per workgroup
+    constexpr int KB = tile<T>::KB;
+    const int K = P * f, Kp = (K + KB - 1) / KB * KB;
+    const int ks_q = g_tune.ksplit_qkv, ks_o = g_tune.ksplit_o, ks_g = g_tune.ksplit_gu;
+    const size_t lds_x = ((size_t)dm + kRedFloats + 16) * sizeof(float);
 
     // optional per-kernel timing: event i is recorded before kernel i, the last event after the last kernel
 #define CQIL_MARK(i) do { if (s.ev) (void)hipEventRecord(s.ev[i], st); } while (0)
     CQIL_MARK(0);
-#define CQIL_QKV(PIPE)                                                                                               \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(qkv_rope_kernel<T, PIPE>), dim3(P * 3 * nh * parts), dim3(kThreads),          \
-                       (xw + dk + 16) * sizeof(float), st, (const T*)s.x_in, wqkv, g_attn, rope, s.kv_len, (T*)s.kc, \
-                       (T*)s.vc, q, dm, nh, dk, d.max_seq, s.b_max, d.rms_eps, parts)
-    switch (pipe) { case 1: CQIL_QKV(1); break; case 2: CQIL_QKV(2); break; case 3: CQIL_QKV(3); break; default: CQIL_QKV(0); }
-#undef CQIL_QKV
+    {
+        const int units = 3 * nh * (dk / 32), uw = kWaves / ks_q;
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(qkv_rope_kernel<T>), dim3((units + uw - 1) / uw, P), dim3(kThreads), lds_x, st,
+                           (const T*)s.x_in, wqkv, g_attn, rope, s.kv_len, (T*)s.kc, (T*)s.vc, q, dm, nh, dk,
+                           d.max_seq, s.b_max, d.rms_eps, ks_q);
+    }
     CQIL_MARK(1);
     const int lps = dk * (int)sizeof(T) / 16;
 #define CQIL_ATTN(LPS)                                                                                               \
@@ -273,25 +272,21 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     }
 #undef CQIL_ATTN
     CQIL_MARK(2);
-#define CQIL_OPROJ(PIPE)                                                                                             \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(oproj_kernel<T, PIPE>), dim3((dm + rows_o - 1) / rows_o, P), dim3(kThreads),  \
-                       xw * sizeof(float), st, ctx, wo, a, P, dm, rows_o)
-    switch (pipe) { case 1: CQIL_OPROJ(1); break; case 2: CQIL_OPROJ(2); break; case 3: CQIL_OPROJ(3); break; default: CQIL_OPROJ(0); }
-#undef CQIL_OPROJ
+    {
+        const int units = dm / 16, uw = kWaves / ks_o;
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(oproj_kernel<T>), dim3((units + uw - 1) / uw, P), dim3(kThreads), lds_x, st,
+                           ctx, wo, a, P, dm, ks_o);
+    }
     CQIL_MARK(3);
-#define CQIL_GATEUP(PIPE)                                                                                            \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(gateup_kernel<T, PIPE>), dim3((f + j_per - 1) / j_per, P), dim3(kThreads),    \
-                       (xw + 16) * sizeof(float), st, (const T*)s.x_in, a, wgu, g_ffn, u, P, bd, dm, f, j_per,       \
-                       d.rms_eps)
-    switch (pipe) { case 1: CQIL_GATEUP(1); break; case 2: CQIL_GATEUP(2); break; case 3: CQIL_GATEUP(3); break; default: CQIL_GATEUP(0); }
-#undef CQIL_GATEUP
+    {
+        const int units = f / kGuBlock, uw = kWaves / ks_g;
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(gateup_kernel<T>), dim3((units + uw - 1) / uw, P), dim3(kThreads), lds_x, st,
+                           (const T*)s.x_in, a, wgu, g_ffn, u, P, bd, dm, f, d.rms_eps, ks_g);
+    }
     CQIL_MARK(4);
-#define CQIL_DOWN(PIPE)                                                                                              \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(down_kernel<T, PIPE>), dim3((dm + rows_d - 1) / rows_d, s.wl.n_slices),       \
-                       dim3(kThreads), ((s.wl.down_slice + 511) & ~511) * sizeof(float), st, u, wdown, dpart, P, dm, \
-                       f, rows_d, s.wl.down_slice)
-    switch (pipe) { case 1: CQIL_DOWN(1); break; case 2: CQIL_DOWN(2); break; case 3: CQIL_DOWN(3); break; default: CQIL_DOWN(0); }
-#undef CQIL_DOWN
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(down_kernel<T>), dim3((dm / 16 + kWaves - 1) / kWaves, s.wl.n_slices),
+                       dim3(kThreads), (size_t)s.wl.down_slice * sizeof(float), st, u, wdown, dpart, K, Kp, dm,
+                       s.wl.down_slice);
     CQIL_MARK(5);
     hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 255) / 256, 1), dim3(256), 0, st, (const T*)s.x_in,
                        a, dpart, (T*)s.x_out, s.kv_len, s.advance, P, s.wl.n_slices, 1, dm, 1, 1);

@@ -42,6 +42,22 @@ template <> struct elem<bf16_t> {
     }
 };
 
+// ---------------------------------------------------------------------------------------------------------
+// Tiled weight layout.  A logical matrix W[R][K] (R a multiple of 16, K padded to Kp, a multiple of the k block
+// KB = 4 * kVec) is stored as 1 KiB tiles of 16 rows x KB columns; the tiles of one 16-row strip follow each other
+// along k.  Inside a tile the order is [g = (k % KB) / kVec][i = r % 16][e = k % kVec], i.e. the 16-byte piece of
+// lane i + 16 g of a wave: one wave-wide 16-byte load reads one whole tile, fully contiguous, and the piece a
+// lane receives is exactly its fragment of the A operand of v_mfma_f32_16x16x32_bf16 (row i, k group g).
+// ---------------------------------------------------------------------------------------------------------
+template <typename T> struct tile {
+    static constexpr int V = 16 / (int)sizeof(T);  // elements per 16-byte piece
+    static constexpr int KB = 4 * V;               // columns per tile (32 for bf16, 16 for fp32)
+    static constexpr int kElems = 16 * KB;         // elements per tile (1 KiB)
+    __host__ __device__ static inline size_t offset(size_t r, size_t k, size_t Kp) {
+        return ((r >> 4) * (Kp / KB) + k / KB) * kElems + ((k % KB) / V) * (16 * V) + (r & 15) * V + (k % V);
+    }
+};
+
 // 16-byte global load of streamed (read-once) data
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load16_stream(const void* p) {

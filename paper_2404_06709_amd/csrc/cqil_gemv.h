@@ -1,5 +1,6 @@
-// Streaming matrix-vector building block shared by the decode kernels: a wave owns four weight rows at a
-// time, each lane reads 16 contiguous bytes of each row per step, the input vector sits in LDS as fp32.
+// Streaming matrix-vector building blocks of the decode kernels.
+// dot4: row-major matrices (the lm head): a wave owns four rows at a time, each lane reads 16 contiguous bytes of
+// each row per step, the input vector sits in LDS as fp32.  tile_strip_dot: the tiled layout of the packed groups.
 #pragma once
 #include "cqil_dev.h"
 
@@ -97,151 +98,65 @@ __device__ __forceinline__ void dot4(const WT* r0, const WT* r1, const WT* r2, c
 __device__ __forceinline__ int xs_words(int len) { return (len + 511) & ~511; }
 
 // ---------------------------------------------------------------------------------------------------------
-// Software-pipelined version of the same block.  A wave walks a sequence of row groups (four rows each) and,
-// inside a group, tiles of two 16-byte steps; the loads of the NEXT tile (of this group or of the wave's next
-// group) are issued before the current tile is consumed, so a wave always has 8 to 16 loads in flight.
-//   rows(g, r)  fills the four row pointers of group g
-//   done(g, s)  receives the four totals of group g (in every lane)
-// Groups g = g_begin, g_begin + g_stride, ... < g_end.
+// Streaming block over the tiled weight layout (tile<> in cqil_dev.h).  A wave walks one 16-row strip: every
+// 16-byte load of the wave reads one whole 1 KiB tile (fully contiguous), U tiles in flight; lane i + 16 g holds
+// kVec columns (k group g) of row i and multiplies them with the matching input values, which sit in LDS as fp32
+// in natural order (the 16 lanes of a k group read the same address: a broadcast).  The four k groups of a row
+// are added with two cross-lane steps; every lane returns the dot product of row (lane % 16) over the n_kb tiles.
+//   strip  first tile of the range;  xs  input values of the first column of the range
 // ---------------------------------------------------------------------------------------------------------
-template <typename WT>
-struct Tile2 {
-    uint4 w[8];
-};
-
-template <typename WT>
-__device__ __forceinline__ void tile_load(Tile2<WT>& t, const WT* const (&r)[4], int k, int len) {
-    constexpr int step = kWave * elem<WT>::kVec;
-    const bool second = k + step < len;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) t.w[j] = load16_stream(r[j] + k);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) t.w[4 + j] = second ? load16_stream(r[j] + k + step) : make_uint4(0, 0, 0, 0);
-}
-
-template <typename WT>
-__device__ __forceinline__ void tile_fma(const Tile2<WT>& t, const float* xs, int k, int len, float (&acc)[4]) {
-    constexpr int V = elem<WT>::kVec;
-    constexpr int step = kWave * V;
-    float x[V], f[V];
-    xs_read<V>(xs, k, x);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        elem<WT>::unpack(t.w[j], f);
-#pragma unroll
-        for (int e = 0; e < V; ++e) acc[j] = fmaf(f[e], x[e], acc[j]);
-    }
-    if (k + step < len) {
-        xs_read<V>(xs, k + step, x);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            elem<WT>::unpack(t.w[4 + j], f);
-#pragma unroll
-            for (int e = 0; e < V; ++e) acc[j] = fmaf(f[e], x[e], acc[j]);
-        }
-    }
-}
-
-template <typename WT, typename RowFn, typename DoneFn>
-__device__ __forceinline__ void stream_groups(int g_begin, int g_end, int g_stride, int len, const float* xs,
-                                              RowFn rows, DoneFn done) {
-    constexpr int V = elem<WT>::kVec;
-    constexpr int step = kWave * V;
+template <typename T, int U>
+__device__ __forceinline__ float tile_strip_dot(const T* __restrict__ strip, int n_kb, const float* xs) {
+    constexpr int V = tile<T>::V, KB = tile<T>::KB, TE = tile<T>::kElems;
     const int lane = threadIdx.x & 63;
-    const int k_lane = lane * V;
-    if (g_begin >= g_end) return;
-    // lanes whose first element lies beyond len idle for the whole call (len < 64*V only in tiny shapes)
-    const bool lane_on = k_lane < len;
-    const WT* r[4];
-    rows(g_begin, r);
-    Tile2<WT> cur;
-    if (lane_on) tile_load<WT>(cur, r, k_lane, len);
-    for (int g = g_begin; g < g_end; g += g_stride) {
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        const WT* rn[4];
-        const bool more_groups = g + g_stride < g_end;
-        if (more_groups) rows(g + g_stride, rn);
-        for (int k = k_lane; k < len; k += 2 * step) {
-            Tile2<WT> nxt;
-            const int kn = k + 2 * step;
-            if (kn < len) tile_load<WT>(nxt, r, kn, len);
-            else if (more_groups) tile_load<WT>(nxt, rn, k_lane, len);
-            tile_fma<WT>(cur, xs, k, len, acc);
-            cur = nxt;
-        }
-        float s[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s[j] = wave_sum(acc[j]);
-        done(g, s);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = rn[j];
-    }
-}
-
-
-// One row at a time: up to NCH 16-byte steps of ONE row in flight per lane (a wave requests NCH KiB of
-// contiguous memory back to back), then the next row.
-template <typename WT, int NCH>
-__device__ __forceinline__ float row_dot(const WT* r, const float* xs, int len) {
-    constexpr int V = elem<WT>::kVec;
-    constexpr int step = kWave * V;
-    const int lane = threadIdx.x & 63;
+    const T* p = strip + lane * V;
+    const float* xg = xs + (lane >> 4) * V;
     float acc = 0.f;
-    for (int k0 = lane * V; k0 < len; k0 += NCH * step) {
-        uint4 w[NCH];
+    int kb = 0;
+    for (; kb + U <= n_kb; kb += U) {
+        uint4 w[U];
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const int k = k0 + c * step;
-            w[c] = k < len ? load16_stream(r + k) : make_uint4(0, 0, 0, 0);
-        }
+        for (int u = 0; u < U; ++u) w[u] = load16_stream(p + (size_t)(kb + u) * TE);
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const int k = k0 + c * step;
-            if (k < len) {
-                float x[V], f[V];
-                xs_read<V>(xs, k, x);
-                elem<WT>::unpack(w[c], f);
+        for (int u = 0; u < U; ++u) {
+            float f[V];
+            elem<T>::unpack(w[u], f);
+            const float* xp = xg + (kb + u) * KB;
 #pragma unroll
-                for (int e = 0; e < V; ++e) acc = fmaf(f[e], x[e], acc);
+            for (int e = 0; e < V; e += 4) {
+                const float4 xv = *reinterpret_cast<const float4*>(xp + e);
+                acc = fmaf(f[e], xv.x, acc);
+                acc = fmaf(f[e + 1], xv.y, acc);
+                acc = fmaf(f[e + 2], xv.z, acc);
+                acc = fmaf(f[e + 3], xv.w, acc);
             }
         }
     }
-    return wave_sum(acc);
-}
-
-template <typename WT, int NCH, typename RowFn, typename DoneFn>
-__device__ __forceinline__ void stream_groups_rowwise(int g_begin, int g_end, int g_stride, int len, const float* xs,
-                                                      RowFn rows, DoneFn done) {
-    for (int g = g_begin; g < g_end; g += g_stride) {
-        const WT* r[4];
-        rows(g, r);
-        float s[4];
+    if (kb < n_kb) {  // ragged end: the remaining tiles in one batch (the conditions are wave-uniform)
+        uint4 w[U];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s[j] = row_dot<WT, NCH>(r[j], xs, len);
-        done(g, s);
+        for (int u = 0; u < U; ++u)
+            if (kb + u < n_kb) w[u] = load16_stream(p + (size_t)(kb + u) * TE);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (kb + u < n_kb) {
+                float f[V];
+                elem<T>::unpack(w[u], f);
+                const float* xp = xg + (kb + u) * KB;
+#pragma unroll
+                for (int e = 0; e < V; e += 4) {
+                    const float4 xv = *reinterpret_cast<const float4*>(xp + e);
+                    acc = fmaf(f[e], xv.x, acc);
+                    acc = fmaf(f[e + 1], xv.y, acc);
+                    acc = fmaf(f[e + 2], xv.z, acc);
+                    acc = fmaf(f[e + 3], xv.w, acc);
+                }
+            }
+        }
     }
-}
-
-// Same interface without the cross-tile prefetch (one dot4 per group).
-template <typename WT, typename RowFn, typename DoneFn>
-__device__ __forceinline__ void stream_groups_simple(int g_begin, int g_end, int g_stride, int len, const float* xs,
-                                                     RowFn rows, DoneFn done) {
-    for (int g = g_begin; g < g_end; g += g_stride) {
-        const WT* r[4];
-        rows(g, r);
-        float s[4];
-        dot4<WT>(r[0], r[1], r[2], r[3], xs, len, s);
-        done(g, s);
-    }
-}
-
-template <typename WT, int PIPE, typename RowFn, typename DoneFn>
-__device__ __forceinline__ void stream_rows(int g_begin, int g_end, int g_stride, int len, const float* xs, RowFn rows,
-                                            DoneFn done) {
-    if constexpr (PIPE == 1) stream_groups<WT>(g_begin, g_end, g_stride, len, xs, rows, done);
-    else if constexpr (PIPE == 2) stream_groups_rowwise<WT, 16>(g_begin, g_end, g_stride, len, xs, rows, done);
-    else if constexpr (PIPE == 3) stream_groups_rowwise<WT, 8>(g_begin, g_end, g_stride, len, xs, rows, done);
-    else stream_groups_simple<WT>(g_begin, g_end, g_stride, len, xs, rows, done);
+    acc += __shfl_xor(acc, 16, kWave);
+    acc += __shfl_xor(acc, 32, kWave);
+    return acc;
 }
 
 }  // namespace cqil

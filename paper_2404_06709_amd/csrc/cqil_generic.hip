@@ -207,16 +207,19 @@ __global__ void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ u, int P
 
 // ------------------------------------------------------------------------------------------ plain GEMM
 // C[m][n] = sum_k A[m][k] * B[n][k]  (+ R[m][n]), fp32 accumulate, 64x64 tile, 16-wide K steps, 4x4 per thread.
-// blockIdx.z selects a group: pointers advance by the given element strides.  K % 4 == 0.
+// A and C are row-major; B is a packed weight matrix in the tiled layout with padded width Kp.  blockIdx.z selects
+// a group: A and C advance by element strides, B by a row offset and a column offset (N- or K-concatenation).
+// K % 4 == 0.
 template <typename AT, typename BT, typename CT, bool ADD_R>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(const AT* __restrict__ A, const BT* __restrict__ B,
                                                       CT* __restrict__ C, const float* __restrict__ R, int M, int N,
-                                                      int K, size_t lda, size_t ldb, size_t ldc, size_t sA, size_t sB,
-                                                      size_t sC) {
+                                                      int K, size_t lda, size_t Kp, size_t ldc, size_t sA,
+                                                      size_t n_step, size_t k_step, size_t sC) {
     constexpr int BM = 64, BN = 64, BK = 16;
     __shared__ float As[BK][BM + 4];
     __shared__ float Bs[BK][BN + 4];
-    A += (size_t)blockIdx.z * sA; B += (size_t)blockIdx.z * sB; C += (size_t)blockIdx.z * sC;
+    A += (size_t)blockIdx.z * sA; C += (size_t)blockIdx.z * sC;
+    const size_t n_off = (size_t)blockIdx.z * n_step, k_off = (size_t)blockIdx.z * k_step;
     const int tid = threadIdx.x;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int tx = tid % 16, ty = tid / 16;
@@ -234,7 +237,11 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const AT* __restrict__ A, 
             const int gn = n0 + lr, gk = k0 + lc;
             float v[4] = {0.f, 0.f, 0.f, 0.f};
             if (gn < N && gk < K)
-                for (int j = 0; j < 4; ++j) v[j] = elem<BT>::load(B + (size_t)gn * ldb + gk + j);
+            {
+                // four consecutive columns of one row lie inside one 16-byte piece of a tile
+                const BT* bp = B + tile<BT>::offset(n_off + gn, k_off + gk, Kp);
+                for (int j = 0; j < 4; ++j) v[j] = elem<BT>::load(bp + j);
+            }
             for (int j = 0; j < 4; ++j) Bs[lc + j][lr] = v[j];
         }
         __syncthreads();
@@ -266,11 +273,11 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const AT* __restrict__ A, 
 }
 
 template <typename AT, typename BT, typename CT, bool ADD_R>
-static void gemm_nt(const AT* A, const BT* B, CT* C, const float* R, int M, int N, int K, size_t lda, size_t ldb,
-                    size_t ldc, int groups, size_t sA, size_t sB, size_t sC, hipStream_t st) {
+static void gemm_nt(const AT* A, const BT* B, CT* C, const float* R, int M, int N, int K, size_t lda, size_t Kp,
+                    size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step, size_t sC, hipStream_t st) {
     dim3 grid((N + 63) / 64, (M + 63) / 64, groups);
     hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_nt_kernel<AT, BT, CT, ADD_R>), grid, dim3(256), 0, st, A, B, C, R, M, N, K,
-                       lda, ldb, ldc, sA, sB, sC);
+                       lda, Kp, ldc, sA, n_step, k_step, sC);
 }
 
 __global__ void advance_kernel(int32_t* kv_len, int B, int T) {
@@ -309,7 +316,7 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     hipLaunchKernelGGL(HIP_KERNEL_NAME(rmsnorm_multi_kernel<T>), dim3(M), dim3(256), 0, st, x, g_attn, nrm, P, M, dm,
                        d.rms_eps);
     gemm_nt<T, T, T, false>(nrm, wqkv, qkv, nullptr, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm,
-                            (size_t)3 * dm * dm, (size_t)3 * dm, st);
+                            (size_t)3 * dm, 0, (size_t)3 * dm, st);
     hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M, P * nh), dim3(((dk / 2) + 63) / 64 * 64), 0, st,
                        qkv, rope, s.kv_len, (T*)s.kc, (T*)s.vc, P, s.T, nh, dk, d.max_seq, s.b_max);
     const int lps = dk * (int)sizeof(T) / 16;
@@ -324,10 +331,10 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
         default: return hipErrorInvalidValue;
     }
 #undef CQIL_ATTN
-    gemm_nt<T, T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, (size_t)dm, Mdm, st);
+    gemm_nt<T, T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, 0, (size_t)dm, Mdm, st);
     hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(256), 0, st, x, a, g_ffn, nrm, resid, P, bd,
                        M, dm, d.rms_eps);
-    gemm_nt<T, T, T, false>(nrm, wgu, gu, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * 2 * f, P, Mdm, (size_t)2 * f * dm,
+    gemm_nt<T, T, T, false>(nrm, wgu, gu, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * 2 * f, P, Mdm, (size_t)2 * f, 0,
                             (size_t)2 * f, st);
     {
         const size_t total = (size_t)M * P * f;
@@ -335,7 +342,10 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
         if (g > 65536) g = 65536;
         hipLaunchKernelGGL(HIP_KERNEL_NAME(swiglu_kernel<T>), dim3((int)g), dim3(256), 0, st, (const T*)gu, u, P, M, f);
     }
-    gemm_nt<T, T, T, true>(u, wdown, (T*)s.x_out, resid, M, dm, P * f, (size_t)P * f, (size_t)P * f, dm, 1, 0, 0, 0, st);
+    {
+        const size_t kt = tile<T>::KB, Kp = ((size_t)P * f + kt - 1) / kt * kt;
+        gemm_nt<T, T, T, true>(u, wdown, (T*)s.x_out, resid, M, dm, P * f, (size_t)P * f, Kp, dm, 1, 0, 0, 0, 0, st);
+    }
     if (s.advance) hipLaunchKernelGGL(advance_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st, s.kv_len, s.B, s.T);
     return hipGetLastError();
 }

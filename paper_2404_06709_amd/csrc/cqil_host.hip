@@ -14,9 +14,9 @@ int check_dims(const cqil_dims* d, int P) {
     if (!d) return CQIL_EINVAL;
     if (P < 1 || P > kMaxP) return CQIL_EINVAL;
     if (d->dtype != CQIL_F32 && d->dtype != CQIL_BF16) return CQIL_EINVAL;
-    if (d->d_model < 8 || d->n_heads < 1 || d->head_dim < 1 || d->d_ffn < 16 || d->max_seq < 1) return CQIL_EINVAL;
+    if (d->d_model < 32 || d->n_heads < 1 || d->head_dim < 32 || d->d_ffn < 16 || d->max_seq < 1) return CQIL_EINVAL;
     if ((long long)d->n_heads * d->head_dim != d->d_model) return CQIL_EINVAL;
-    if (d->d_model % 8 || d->d_ffn % kGuBlock) return CQIL_EINVAL;
+    if (d->d_model % 32 || d->d_ffn % kGuBlock) return CQIL_EINVAL;  // whole tiles of the packed layout
     if (d->d_model > 14336) return CQIL_EINVAL;  // the normalised input of a projection sits in LDS as fp32
     // lanes sharing one cache slot in the attention kernels: head_dim * esize / 16 must be 4, 8, 16 or 32
     const int lps = d->head_dim * (int)esize(d->dtype) / 16;
@@ -34,7 +34,9 @@ static int packed_layout(const cqil_dims* d, int P, cqil_packed_layout* L) {
     L->wqkv = off;   off = align_up(off + (size_t)P * 3 * dm * dm * es);
     L->wo = off;     off = align_up(off + (size_t)P * dm * dm * es);
     L->wgu = off;    off = align_up(off + (size_t)P * 2 * f * dm * es);
-    L->wdown = off;  off = align_up(off + (size_t)P * dm * f * es);
+    const size_t kb = 64 / es;  // columns per tile; the concatenated K of Wdown is padded to whole tiles
+    const size_t kp_down = ((size_t)P * f + kb - 1) / kb * kb;
+    L->wdown = off;  off = align_up(off + dm * kp_down * es);
     L->g_attn = off; off = align_up(off + (size_t)P * dm * es);
     L->g_ffn = off;  off = align_up(off + (size_t)P * dm * es);
     L->rope = off;   off = align_up(off + (size_t)d->max_seq * (d->head_dim / 2) * 2 * sizeof(float));
@@ -50,21 +52,23 @@ int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* W) {
     const size_t M = (size_t)B * T, dm = d->d_model, f = d->d_ffn, es = esize(d->dtype);
     memset(W, 0, sizeof(*W));
     const size_t K = (size_t)P * f;
+    const size_t ktile = 64 / es;
+    const size_t Kp = (K + ktile - 1) / ktile * ktile;  // padded K of the packed Wdown (whole tiles)
     // K slices of the decode down projection: equal lengths, multiples of 512, at most the tuned maximum
     const size_t smax = (size_t)g_tune.down_slice_max;
-    int ns = (int)((K + smax - 1) / smax);
-    size_t sl = ((K + ns - 1) / ns + 511) / 512 * 512;
-    ns = (int)((K + sl - 1) / sl);
+    int ns = (int)((Kp + smax - 1) / smax);
+    size_t sl = ((Kp + ns - 1) / ns + 511) / 512 * 512;
+    ns = (int)((Kp + sl - 1) / sl);
     W->n_slices = ns;
     W->down_slice = (int)sl;
     size_t off = 0;
     W->q = off;         off = align_up(off + (size_t)P * M * dm * sizeof(float));
     W->ctx = off;       off = align_up(off + (size_t)P * M * dm * sizeof(float));
     W->a = off;         off = align_up(off + (size_t)P * M * dm * sizeof(float));
-    // small-batch path: slices of at most 4096, equal lengths, multiples of 128
-    int sks = (int)((K + 4095) / 4096);
-    size_t skl = ((K + sks - 1) / sks + 127) / 128 * 128;
-    sks = (int)((K + skl - 1) / skl);
+    // small-batch path: slices of at most 4096 columns, equal lengths, multiples of 256 (8 tiles)
+    int sks = (int)((Kp + 4095) / 4096);
+    size_t skl = ((Kp + sks - 1) / sks + 255) / 256 * 256;
+    sks = (int)((Kp + skl - 1) / skl);
     W->sk_slices = sks;
     W->sk_slice = (int)skl;
     if (M == 1) {
@@ -109,22 +113,19 @@ const char* cqil_strerror(int status) {
 
 int cqil_set_tuning(const char* key, int value) {
     if (!key) return CQIL_EINVAL;
-    if (!strcmp(key, "rows_o") || !strcmp(key, "rows_d")) {
-        const bool is_o = key[5] == 'o';
-        if (!(is_o && value == 0) && (value < 16 || value > 4096 || value % 16)) return CQIL_EINVAL;
-        (is_o ? g_tune.rows_o : g_tune.rows_d) = value;
-    } else if (!strcmp(key, "j_per")) {
-        if (value != 0 && (value < 8 || value > 4096 || value % 8)) return CQIL_EINVAL;
-        g_tune.j_per = value;
+    const bool split_ok = value == 1 || value == 2 || value == 4 || value == 8;
+    if (!strcmp(key, "ksplit_qkv")) {
+        if (!split_ok) return CQIL_EINVAL;
+        g_tune.ksplit_qkv = value;
+    } else if (!strcmp(key, "ksplit_o")) {
+        if (!split_ok) return CQIL_EINVAL;
+        g_tune.ksplit_o = value;
+    } else if (!strcmp(key, "ksplit_gu")) {
+        if (!split_ok) return CQIL_EINVAL;
+        g_tune.ksplit_gu = value;
     } else if (!strcmp(key, "down_slice_max")) {
         if (value < 512 || value > 12288 || value % 512) return CQIL_EINVAL;
         g_tune.down_slice_max = value;
-    } else if (!strcmp(key, "qkv_parts")) {
-        if (value != 1 && value != 2 && value != 4) return CQIL_EINVAL;
-        g_tune.qkv_parts = value;
-    } else if (!strcmp(key, "pipeline")) {
-        if (value < 0 || value > 3) return CQIL_EINVAL;
-        g_tune.pipeline = value;
     } else {
         return CQIL_EINVAL;
     }

@@ -15,12 +15,11 @@ inline size_t esize(int dtype) { return dtype == CQIL_BF16 ? 2 : 4; }
 constexpr int kGuBlock = 16;        // gate/up rows are interleaved in blocks of this many rows
 constexpr int kMaxP = 16;
 
-// Launch-shape knobs of the decode kernels (cqil_set_tuning).  rows_o / rows_d: weight rows per workgroup of the
-// O and down projections (multiples of 16); j_per: gate/up row pairs per workgroup (multiple of 8);
-// down_slice_max: longest K slice of the down projection (multiple of 512, at most 12288); pipeline: 1 = loads
-// of the next tile are issued before the current one is consumed.
+// Launch-shape knobs of the single-token decode kernels (cqil_set_tuning): waves that share one unit of work
+// (k split: 1, 2, 4 or 8) in the QKV, O and gate/up kernels, and the longest K slice of the down projection
+// (multiple of 512, at most 12288).
 struct Tuning {
-    int rows_o = 0, rows_d = 32, j_per = 0, down_slice_max = 6144, pipeline = 0, qkv_parts = 2;  // 0 = by shape
+    int ksplit_qkv = 2, ksplit_o = 4, ksplit_gu = 1, down_slice_max = 6144;
 };
 extern Tuning g_tune;
 

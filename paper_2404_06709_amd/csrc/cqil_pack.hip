@@ -1,10 +1,12 @@
 // cqil_pack_group: one-time packing of P layers' weights into the group layout.
 //
-// The paper places layer l+i of a group on GPU i (Alg.1).  On one GPU the same independence is
-// expressed by concatenation: projections that read the shared input (Wq, Wk, Wv; Wgate, Wup) are
-// stacked along their output dimension, and the projections whose results Eq.3 / Eq.4 sum over the
-// group (Wo, Wdown) are laid side by side along their input dimension, so that the sum over layers is
-// part of one long dot product.  Everything here is a pure index map on 16-byte vectors.
+// The paper places layer l+i of a group on GPU i (Alg.1).  On one GPU the same independence is expressed by
+// concatenation: projections that read the shared input (Wq, Wk, Wv; Wgate, Wup) are stacked along their output
+// dimension, and the projections whose results Eq.3 / Eq.4 sum over the group (Wo, Wdown) are laid side by side
+// along their input dimension, so that the sum over layers is part of one long dot product.  Each concatenated
+// matrix is then stored in 1 KiB tiles of 16 rows (see tile<> in cqil_dev.h) so that a 64-lane wave streams it with
+// fully contiguous 16-byte loads and receives matrix-core operand fragments directly.  Everything here is a pure
+// index map on 16-byte pieces (8 bf16 or 4 fp32 values of one source row); padding columns are zero.
 #include "cqil_dev.h"
 #include "cqil_internal.h"
 
@@ -14,44 +16,50 @@ struct PackPtrs {
     const char* p[kMaxP];
 };
 
-// dst[(l*3 + m)][o][:] = W_m of layer l, row o          (m = 0,1,2 for q,k,v)
-__global__ void pack_qkv_kernel(PackPtrs wq, PackPtrs wk, PackPtrs wv, uint4* dst, int P, int d_model, int vec_per_row) {
-    const size_t per_mat = (size_t)d_model * vec_per_row;
-    const size_t total = per_mat * 3 * (size_t)P;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const size_t mat = i / per_mat, within = i - mat * per_mat;
-        const int l = (int)(mat / 3), m = (int)(mat % 3);
-        const char* src = m == 0 ? wq.p[l] : (m == 1 ? wk.p[l] : wv.p[l]);
-        dst[i] = reinterpret_cast<const uint4*>(src)[within];
-    }
-}
+enum PackKind { kPackQkv = 0, kPackWo = 1, kPackGu = 2, kPackDown = 3 };
 
-// dst[o][l][:] = W of layer l, row o   (rows of `cols` elements; used for Wo and Wdown)
-__global__ void pack_kcat_kernel(PackPtrs w, uint4* dst, int P, int rows, int vec_per_row) {
-    const size_t total = (size_t)rows * P * vec_per_row;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const size_t v = i % vec_per_row;
-        const size_t ol = i / vec_per_row;
-        const int l = (int)(ol % P);
-        const size_t o = ol / P;
-        dst[i] = reinterpret_cast<const uint4*>(w.p[l])[o * vec_per_row + v];
-    }
-}
-
-// dst[l][j/16][gu][j%16][:] = (gu ? Wup : Wgate) of layer l, row j
-__global__ void pack_gu_kernel(PackPtrs wg, PackPtrs wu, uint4* dst, int P, int d_ffn, int vec_per_row) {
-    const size_t total = (size_t)P * 2 * d_ffn * vec_per_row;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const size_t v = i % vec_per_row;
-        size_t r = i / vec_per_row;  // packed row
-        const int l = (int)(r / (2 * (size_t)d_ffn));
-        r -= (size_t)l * 2 * d_ffn;
-        const int blk = (int)(r / (2 * kGuBlock));
-        const int in = (int)(r % (2 * kGuBlock));
-        const int gu = in / kGuBlock;
-        const int j = blk * kGuBlock + in % kGuBlock;
-        const char* src = gu ? wu.p[l] : wg.p[l];
-        dst[i] = reinterpret_cast<const uint4*>(src)[(size_t)j * vec_per_row + v];
+// One thread per destination 16-byte piece.  The destination piece index decomposes as
+// (row strip rt, k block kb, k group g, row in strip i); logical row r = 16 rt + i, first column k = KB kb + V g.
+//   kPackQkv : rows [l][q|k|v][o], K = d_model          source row o of W_m of layer l
+//   kPackWo  : rows o, K = [l][d_model]                 source row o of Wo of layer l
+//   kPackGu  : rows [l][j/16][gate|up][j%16], K = d_model
+//   kPackDown: rows o, K = [l][d_ffn] (+ zero padding)  source row o of Wdown of layer l
+template <int KIND, int V>
+__global__ void pack_tiled_kernel(PackPtrs s0, PackPtrs s1, PackPtrs s2, uint4* __restrict__ dst, int P, int d_model,
+                                  int d_ffn, size_t n_rows, size_t Kp) {
+    constexpr int KB = 4 * V;
+    const size_t kblocks = Kp / KB;
+    const size_t total = n_rows * kblocks * 4;  // pieces: per row KB/V = 4 per k block
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int i = (int)(idx & 15);
+        const int g = (int)((idx >> 4) & 3);
+        const size_t tile_id = idx >> 6;
+        const size_t kb = tile_id % kblocks, rt = tile_id / kblocks;
+        const size_t r = rt * 16 + i;
+        const size_t k = kb * KB + (size_t)g * V;
+        const uint4* src = nullptr;  // 16-byte piece of a source row, or null for padding
+        if (KIND == kPackQkv) {
+            const int lm = (int)(r / d_model), o = (int)(r % d_model);
+            const int l = lm / 3, m = lm % 3;
+            const char* base = m == 0 ? s0.p[l] : (m == 1 ? s1.p[l] : s2.p[l]);
+            src = reinterpret_cast<const uint4*>(base) + ((size_t)o * d_model + k) / V;
+        } else if (KIND == kPackWo) {
+            const int l = (int)(k / d_model), kk = (int)(k % d_model);
+            src = reinterpret_cast<const uint4*>(s0.p[l]) + (r * d_model + kk) / V;
+        } else if (KIND == kPackGu) {
+            const int l = (int)(r / (2 * (size_t)d_ffn));
+            const int in = (int)(r % (2 * (size_t)d_ffn));
+            const int blk = in / (2 * kGuBlock), w = in % (2 * kGuBlock);
+            const int j = blk * kGuBlock + w % kGuBlock;
+            const char* base = (w / kGuBlock) ? s1.p[l] : s0.p[l];
+            src = reinterpret_cast<const uint4*>(base) + ((size_t)j * d_model + k) / V;
+        } else {
+            if (k < (size_t)P * d_ffn) {
+                const int l = (int)(k / d_ffn), j = (int)(k % d_ffn);
+                src = reinterpret_cast<const uint4*>(s0.p[l]) + (r * d_ffn + j) / V;
+            }
+        }
+        dst[idx] = src ? *src : make_uint4(0, 0, 0, 0);
     }
 }
 
@@ -80,37 +88,44 @@ static int grid_for(size_t total, int threads) {
     return (int)g;
 }
 
+template <int V>
+static void pack_all(const cqil_dims& d, int P, const PackArgs& src, char* packed, const cqil_packed_layout& L,
+                     hipStream_t st) {
+    constexpr int KB = 4 * V;
+    const int T = 256, dm = d.d_model, f = d.d_ffn;
+    PackPtrs a, b, c;
+    for (int l = 0; l < P; ++l) { a.p[l] = (const char*)src.layers[l].wq; b.p[l] = (const char*)src.layers[l].wk; c.p[l] = (const char*)src.layers[l].wv; }
+    size_t rows = (size_t)P * 3 * dm, Kp = dm;
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(pack_tiled_kernel<kPackQkv, V>), dim3(grid_for(rows * Kp / V, T)), dim3(T), 0, st,
+                       a, b, c, (uint4*)(packed + L.wqkv), P, dm, f, rows, Kp);
+    for (int l = 0; l < P; ++l) a.p[l] = (const char*)src.layers[l].wo;
+    rows = dm; Kp = (size_t)P * dm;
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(pack_tiled_kernel<kPackWo, V>), dim3(grid_for(rows * Kp / V, T)), dim3(T), 0, st,
+                       a, a, a, (uint4*)(packed + L.wo), P, dm, f, rows, Kp);
+    for (int l = 0; l < P; ++l) { a.p[l] = (const char*)src.layers[l].wgate; b.p[l] = (const char*)src.layers[l].wup; }
+    rows = (size_t)P * 2 * f; Kp = dm;
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(pack_tiled_kernel<kPackGu, V>), dim3(grid_for(rows * Kp / V, T)), dim3(T), 0, st,
+                       a, b, b, (uint4*)(packed + L.wgu), P, dm, f, rows, Kp);
+    for (int l = 0; l < P; ++l) a.p[l] = (const char*)src.layers[l].wdown;
+    rows = dm; Kp = ((size_t)P * f + KB - 1) / KB * KB;
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(pack_tiled_kernel<kPackDown, V>), dim3(grid_for(rows * Kp / V, T)), dim3(T), 0,
+                       st, a, a, a, (uint4*)(packed + L.wdown), P, dm, f, rows, Kp);
+}
+
 hipError_t launch_pack(const cqil_dims& d, int P, const PackArgs& src, char* packed, const cqil_packed_layout& L,
                        hipStream_t st) {
+    if (d.dtype == CQIL_BF16) pack_all<8>(d, P, src, packed, L, st);
+    else pack_all<4>(d, P, src, packed, L, st);
     const int es = (int)esize(d.dtype);
-    const int vpr_dm = d.d_model * es / 16;  // 16-byte vectors per row of d_model elements
-    const int vpr_f = d.d_ffn * es / 16;
-    PackPtrs a, b, c;
+    const int vpr_dm = d.d_model * es / 16;
     const int T = 256;
-
-    for (int l = 0; l < P; ++l) { a.p[l] = (const char*)src.layers[l].wq; b.p[l] = (const char*)src.layers[l].wk; c.p[l] = (const char*)src.layers[l].wv; }
-    hipLaunchKernelGGL(pack_qkv_kernel, dim3(grid_for((size_t)P * 3 * d.d_model * vpr_dm, T)), dim3(T), 0, st, a, b, c,
-                       (uint4*)(packed + L.wqkv), P, d.d_model, vpr_dm);
-
-    for (int l = 0; l < P; ++l) a.p[l] = (const char*)src.layers[l].wo;
-    hipLaunchKernelGGL(pack_kcat_kernel, dim3(grid_for((size_t)P * d.d_model * vpr_dm, T)), dim3(T), 0, st, a,
-                       (uint4*)(packed + L.wo), P, d.d_model, vpr_dm);
-
-    for (int l = 0; l < P; ++l) { a.p[l] = (const char*)src.layers[l].wgate; b.p[l] = (const char*)src.layers[l].wup; }
-    hipLaunchKernelGGL(pack_gu_kernel, dim3(grid_for((size_t)P * 2 * d.d_ffn * vpr_dm, T)), dim3(T), 0, st, a, b,
-                       (uint4*)(packed + L.wgu), P, d.d_ffn, vpr_dm);
-
-    for (int l = 0; l < P; ++l) a.p[l] = (const char*)src.layers[l].wdown;
-    hipLaunchKernelGGL(pack_kcat_kernel, dim3(grid_for((size_t)P * d.d_model * vpr_f, T)), dim3(T), 0, st, a,
-                       (uint4*)(packed + L.wdown), P, d.d_model, vpr_f);
-
+    PackPtrs a;
     for (int l = 0; l < P; ++l) a.p[l] = (const char*)src.layers[l].g_attn;
     hipLaunchKernelGGL(pack_gain_kernel, dim3(grid_for((size_t)P * vpr_dm, T)), dim3(T), 0, st, a,
                        (uint4*)(packed + L.g_attn), P, vpr_dm);
     for (int l = 0; l < P; ++l) a.p[l] = (const char*)src.layers[l].g_ffn;
     hipLaunchKernelGGL(pack_gain_kernel, dim3(grid_for((size_t)P * vpr_dm, T)), dim3(T), 0, st, a,
                        (uint4*)(packed + L.g_ffn), P, vpr_dm);
-
     hipLaunchKernelGGL(rope_table_kernel, dim3(grid_for((size_t)d.max_seq * (d.head_dim / 2), T)), dim3(T), 0, st,
                        (float2*)(packed + L.rope), d.max_seq, d.head_dim / 2, (double)d.rope_base);
     return hipGetLastError();

@@ -2,13 +2,13 @@
 // as the single-token path, with the projections on the matrix cores.
 //
 // The step stays HBM-bound (every weight byte is still read once), but M dot products per weight would saturate
-// the vector ALUs, so each wave multiplies a 16-row weight tile by the M token columns with
-// v_mfma_f32_16x16x32_bf16: the weights are the A operand straight from global memory (each lane reads 64
-// contiguous bytes of one row per step), the activations are the B operand from LDS (bf16, one row per token,
-// columns beyond M are zero).  The order of the k index inside a 128-wide step is the same for both operands,
-// which is all the instruction needs.
+// the vector ALUs, so each wave multiplies 16-row weight strips by the M token columns with
+// v_mfma_f32_16x16x32_bf16.  The packed weights are already stored as the instruction's A operand: one
+// wave-wide 16-byte load reads one contiguous 1 KiB tile and lane i + 16 g receives row i, k group g (tile<> in
+// cqil_dev.h).  The activations are the B operand, read from LDS (bf16, one row per token; columns beyond M are
+// zero).
 //   D[i][j] lands in lane j + 16*(i/4), register i%4: a lane holds four consecutive weight rows of one token, so
-//   the rotary pairs (tiles t and t + head_dim/32) and the gate/up pairs (the packed 16-row blocks) meet in one lane.
+//   the rotary pairs (strips t and t + head_dim/32) and the gate/up pairs (the packed 16-row blocks) meet in one lane.
 #include "cqil_attn.h"
 #include "cqil_dev.h"
 #include "cqil_internal.h"
@@ -18,72 +18,87 @@ namespace cqil {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kSkPad = 8;  // bf16 elements of padding per LDS activation row (keeps rows 16-byte aligned)
+constexpr int kSkPad = 32;  // bf16 elements of padding per LDS activation row (64 bytes: spreads the rows over banks)
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8_t, v); }
 
-// NT tiles of 16 weight rows times the token columns over k in [0, len), len a multiple of 128.
-//   rowp[t]  this lane's weight row (tile row lane%16) advanced to k offset 32*(lane/16)
-//   xrow     this lane's token row in LDS advanced to the same offset; tok_on false -> column of zeros
-template <int NT>
-__device__ __forceinline__ void mfma_rows(const bf16_t* const (&rowp)[NT], const bf16_t* xrow, bool tok_on, int len,
-                                          f32x4_t (&acc)[NT]) {
+// NT strips of 16 weight rows times the token columns over n_kb tiles (32 columns each), U tiles of every strip in
+// flight.
+//   strip[t]  first tile of the range of strip t
+//   xrow      this lane's token row in LDS at the first column of the range plus 8*(lane/16); tok_on false ->
+//             column of zeros (token index >= M)
+template <int NT, int U>
+__device__ __forceinline__ void mfma_strips(const bf16_t* const (&strip)[NT], int n_kb, const bf16_t* xrow, bool tok_on,
+                                            f32x4_t (&acc)[NT]) {
+    constexpr int TE = tile<bf16_t>::kElems, KB = tile<bf16_t>::KB;
     const uint4 zero = make_uint4(0, 0, 0, 0);
-    int kb = 0;
-    for (; kb + 128 < len; kb += 256) {
-        uint4 a0[NT][4], a1[NT][4], b0[4], b1[4];
+    const int lane = threadIdx.x & 63;
+    for (int kb = 0; kb < n_kb; kb += U) {
+        uint4 a[NT][U], b[U];
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int m = 0; m < 4; ++m) a0[t][m] = load16_stream(rowp[t] + kb + 8 * m);
+            for (int u = 0; u < U; ++u)
+                a[t][u] = (kb + u < n_kb) ? load16_stream(strip[t] + (size_t)(kb + u) * TE + lane * 8) : zero;
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+        for (int u = 0; u < U; ++u)
+            b[u] = (tok_on && kb + u < n_kb) ? *reinterpret_cast<const uint4*>(xrow + (kb + u) * KB) : zero;
 #pragma unroll
-            for (int m = 0; m < 4; ++m) a1[t][m] = load16_stream(rowp[t] + kb + 128 + 8 * m);
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            b0[m] = tok_on ? *reinterpret_cast<const uint4*>(xrow + kb + 8 * m) : zero;
-            b1[m] = tok_on ? *reinterpret_cast<const uint4*>(xrow + kb + 128 + 8 * m) : zero;
-        }
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int t = 0; t < NT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0[t][m]), as_bf16x8(b0[m]), acc[t], 0, 0, 0);
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a1[t][m]), as_bf16x8(b1[m]), acc[t], 0, 0, 0);
-    }
-    if (kb < len) {
-        uint4 a0[NT][4], b0[4];
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int m = 0; m < 4; ++m) a0[t][m] = load16_stream(rowp[t] + kb + 8 * m);
-#pragma unroll
-        for (int m = 0; m < 4; ++m) b0[m] = tok_on ? *reinterpret_cast<const uint4*>(xrow + kb + 8 * m) : zero;
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0[t][m]), as_bf16x8(b0[m]), acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[t][u]), as_bf16x8(b[u]), acc[t], 0, 0, 0);
     }
 }
 
-// per-token 1/rms: wave w reduces token w (M <= number of waves); result in rs[] after the barrier
-template <typename F>
-__device__ __forceinline__ void token_rms(F value, int M, int d_model, float eps, float* rs) {
+__device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) { elem<bf16_t>::unpack(v, f); }
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+    uint4 v;
+    v.x = (uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16);
+    v.y = (uint32_t)f32_to_bf16(f[2]) | ((uint32_t)f32_to_bf16(f[3]) << 16);
+    v.z = (uint32_t)f32_to_bf16(f[4]) | ((uint32_t)f32_to_bf16(f[5]) << 16);
+    v.w = (uint32_t)f32_to_bf16(f[6]) | ((uint32_t)f32_to_bf16(f[7]) << 16);
+    return v;
+}
+__device__ __forceinline__ void load8_f32(const float* p, float (&f)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+}
+
+// Builds the LDS activation rows: a wave takes whole token rows (w, w + NW, ...), 8 elements per lane and step
+// with 16-byte loads.  With NORM the row is RMS-normalised and multiplied by the gain (two passes over the row:
+// statistic, then values).  load8(j, v, out) supplies elements 8v .. 8v+7 of token row j.  Ends with a barrier.
+template <bool NORM, typename Load8>
+__device__ __forceinline__ void fill_rows(bf16_t* xs, int kpad, int M, int d_model, float eps, const bf16_t* gain,
+                                          int n_waves, Load8 load8) {
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (w < M) {
-        float ss = 0.f;
-        for (int k = lane; k < d_model; k += kWave) {
-            const float v = value(w, k);
-            ss += v * v;
+    const int nvec = d_model / 8;
+    for (int j = w; j < M; j += n_waves) {
+        float r = 1.0f;
+        if (NORM) {
+            float ss = 0.f;
+#pragma unroll 4
+            for (int v = lane; v < nvec; v += kWave) {
+                float h[8];
+                load8(j, v, h);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss = fmaf(h[e], h[e], ss);
+            }
+            ss = wave_sum(ss);
+            r = 1.0f / sqrtf(ss / (float)d_model + eps);
         }
-        ss = wave_sum(ss);
-        if (lane == 0) rs[w] = 1.0f / sqrtf(ss / (float)d_model + eps);
+#pragma unroll 4
+        for (int v = lane; v < nvec; v += kWave) {
+            float h[8];
+            load8(j, v, h);
+            if (NORM) {
+                float g[8];
+                unpack8(*reinterpret_cast<const uint4*>(gain + 8 * v), g);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) h[e] = h[e] * r * g[e];
+            }
+            *reinterpret_cast<uint4*>(xs + (size_t)j * kpad + 8 * v) = pack8(h);
+        }
     }
     __syncthreads();
 }
@@ -101,16 +116,11 @@ __global__ __launch_bounds__(NW * 64) void qkv_skinny_kernel(
     extern __shared__ __align__(16) unsigned char smem_raw[];
     bf16_t* xs = reinterpret_cast<bf16_t*>(smem_raw);
     const int kpad = d_model + kSkPad;
-    float* rs = reinterpret_cast<float*>(xs + (size_t)8 * kpad);
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int l = blockIdx.y;
-    token_rms([&](int j, int k) { return bf16_to_f32(x[(size_t)j * d_model + k]); }, M, d_model, eps, rs);
-    const bf16_t* g = g_attn + (size_t)l * d_model;
-    for (int idx = tid; idx < M * d_model; idx += NW * 64) {
-        const int j = idx / d_model, k = idx - j * d_model;
-        xs[(size_t)j * kpad + k] = f32_to_bf16(bf16_to_f32(x[idx]) * rs[j] * bf16_to_f32(g[k]));
-    }
-    __syncthreads();
+    fill_rows<true>(xs, kpad, M, d_model, eps, g_attn + (size_t)l * d_model, NW, [&](int j, int v, float (&h)[8]) {
+        unpack8(*reinterpret_cast<const uint4*>(x + (size_t)j * d_model + 8 * v), h);
+    });
 
     const int half = d_k >> 1;
     const int pairs_per_head = half / 16;
@@ -121,11 +131,13 @@ __global__ __launch_bounds__(NW * 64) void qkv_skinny_kernel(
     const int hu = pi / pairs_per_head;
     const int h = hu % n_heads, m3 = hu / n_heads;  // 0,1,2 = q,k,v
     const int i = lane & 15, gq = lane >> 4;
-    const bf16_t* base = wqkv + (((size_t)(l * 3 + m3) * d_model) + (size_t)h * d_k + 16 * tp + i) * d_model + 32 * gq;
-    const bf16_t* rowp[2] = {base, base + (size_t)half * d_model};
+    const int nkb = d_model / 32;
+    const size_t strip_a = ((size_t)(l * 3 + m3) * d_model + (size_t)h * d_k + 16 * tp) / 16;
+    const bf16_t* strip[2] = {wqkv + strip_a * nkb * tile<bf16_t>::kElems,
+                              wqkv + (strip_a + half / 16) * nkb * tile<bf16_t>::kElems};
     f32x4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
     const int j = i;  // token column of this lane
-    mfma_rows<2>(rowp, xs + (size_t)j * kpad + 32 * gq, j < M, d_model, acc);
+    mfma_strips<2, 8>(strip, nkb, xs + (size_t)j * kpad + 8 * gq, j < M, acc);
 
     if (j < M) {
         const int b = j / T_new, t = j % T_new;
@@ -170,18 +182,15 @@ __global__ __launch_bounds__(NW * 64) void oproj_skinny_kernel(const float* __re
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int l = blockIdx.y;
     const float* c = ctx + (size_t)l * M * d_model;
-    for (int idx = tid; idx < M * d_model; idx += NW * 64) {
-        const int j = idx / d_model, k = idx - j * d_model;
-        xs[(size_t)j * kpad + k] = f32_to_bf16(c[idx]);
-    }
-    __syncthreads();
+    fill_rows<false>(xs, kpad, M, d_model, 0.f, nullptr, NW,
+                     [&](int j, int v, float (&h)[8]) { load8_f32(c + (size_t)j * d_model + 8 * v, h); });
     const int ti = blockIdx.x * NW + w;
     if (ti >= d_model / 16) return;
     const int i = lane & 15, gq = lane >> 4;
-    const size_t ld = (size_t)P * d_model;
-    const bf16_t* rowp[1] = {wo + (size_t)(16 * ti + i) * ld + (size_t)l * d_model + 32 * gq};
+    const int nkb = d_model / 32;  // tiles of one layer; a strip holds the P layers' tiles one after the other
+    const bf16_t* strip[1] = {wo + ((size_t)ti * P * nkb + (size_t)l * nkb) * tile<bf16_t>::kElems};
     f32x4_t acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-    mfma_rows<1>(rowp, xs + (size_t)i * kpad + 32 * gq, i < M, d_model, acc);
+    mfma_strips<1, 8>(strip, nkb, xs + (size_t)i * kpad + 8 * gq, i < M, acc);
     if (i < M) {
         float* dst = a + ((size_t)l * M + i) * d_model + 16 * ti + 4 * gq;
         *reinterpret_cast<float4*>(dst) = make_float4(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
@@ -202,31 +211,28 @@ __global__ __launch_bounds__(NW * 64) void gateup_skinny_kernel(const bf16_t* __
     extern __shared__ __align__(16) unsigned char smem_raw[];
     bf16_t* xs = reinterpret_cast<bf16_t*>(smem_raw);
     const int kpad = d_model + kSkPad;
-    float* rs = reinterpret_cast<float*>(xs + (size_t)8 * kpad);
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int l = blockIdx.y;
     const int jlo = max(0, l - bypass_d);
     const size_t Md = (size_t)M * d_model;
-    auto hval = [&](int j, int k) {
-        const size_t idx = (size_t)j * d_model + k;
-        float hv = bf16_to_f32(x[idx]);
-        for (int jj = jlo; jj <= l; ++jj) hv += a[(size_t)jj * Md + idx];
-        return hv;
-    };
-    token_rms(hval, M, d_model, eps, rs);
-    const bf16_t* g = g_ffn + (size_t)l * d_model;
-    for (int idx = tid; idx < M * d_model; idx += NW * 64) {
-        const int j = idx / d_model, k = idx - j * d_model;
-        xs[(size_t)j * kpad + k] = f32_to_bf16(hval(j, k) * rs[j] * bf16_to_f32(g[k]));
-    }
-    __syncthreads();
+    fill_rows<true>(xs, kpad, M, d_model, eps, g_ffn + (size_t)l * d_model, NW, [&](int j, int v, float (&h)[8]) {
+        const size_t idx = (size_t)j * d_model + 8 * v;
+        unpack8(*reinterpret_cast<const uint4*>(x + idx), h);
+        for (int jj = jlo; jj <= l; ++jj) {
+            float t[8];
+            load8_f32(a + (size_t)jj * Md + idx, t);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] += t[e];
+        }
+    });
     const int jb = blockIdx.x * NW + w;  // block of 16 feed-forward units
     if (jb >= d_ffn / kGuBlock) return;
     const int i = lane & 15, gq = lane >> 4;
-    const bf16_t* base = wgu + ((size_t)l * 2 * d_ffn + (size_t)jb * 2 * kGuBlock + i) * d_model + 32 * gq;
-    const bf16_t* rowp[2] = {base, base + (size_t)kGuBlock * d_model};
+    const int nkb = d_model / 32;
+    const size_t strip_g = (size_t)l * 2 * d_ffn / 16 + 2 * (size_t)jb;  // gate strip; the up strip follows it
+    const bf16_t* strip[2] = {wgu + strip_g * nkb * tile<bf16_t>::kElems, wgu + (strip_g + 1) * nkb * tile<bf16_t>::kElems};
     f32x4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-    mfma_rows<2>(rowp, xs + (size_t)i * kpad + 32 * gq, i < M, d_model, acc);
+    mfma_strips<2, 8>(strip, nkb, xs + (size_t)i * kpad + 8 * gq, i < M, acc);
     if (i < M) {
         bf16_t* dst = u + (size_t)i * P * d_ffn + (size_t)l * d_ffn + jb * kGuBlock + 4 * gq;
 #pragma unroll
@@ -251,21 +257,23 @@ __global__ __launch_bounds__(NW * 64) void down_skinny_kernel(const bf16_t* __re
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int slice = blockIdx.y;
     const int k0 = slice * slice_len;
-    const int len = min(slice_len, K - k0);
+    const int Kp = (K + 31) / 32 * 32;        // the packed matrix is zero-padded to whole tiles
+    const int len = min(slice_len, Kp - k0);  // multiple of 32
     const int kpad = slice_len + kSkPad;
     const int vec = len / 8;  // 16-byte vectors per token row of this slice
     for (int idx = tid; idx < M * vec; idx += NW * 64) {
         const int j = idx / vec, v = idx - j * vec;
+        const int k = k0 + 8 * v;
         *reinterpret_cast<uint4*>(xs + (size_t)j * kpad + 8 * v) =
-            *reinterpret_cast<const uint4*>(u + (size_t)j * K + k0 + 8 * v);
+            k < K ? *reinterpret_cast<const uint4*>(u + (size_t)j * K + k) : make_uint4(0, 0, 0, 0);
     }
     __syncthreads();
     const int ti = blockIdx.x * NW + w;
     if (ti >= d_model / 16) return;
     const int i = lane & 15, gq = lane >> 4;
-    const bf16_t* rowp[1] = {wdown + (size_t)(16 * ti + i) * K + k0 + 32 * gq};
+    const bf16_t* strip[1] = {wdown + ((size_t)ti * (Kp / 32) + k0 / 32) * tile<bf16_t>::kElems};
     f32x4_t acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-    mfma_rows<1>(rowp, xs + (size_t)i * kpad + 32 * gq, i < M, len, acc);
+    mfma_strips<1, 8>(strip, len / 32, xs + (size_t)i * kpad + 8 * gq, i < M, acc);
     if (i < M) {
         float* dst = part + ((size_t)slice * M + i) * d_model + 16 * ti + 4 * gq;
         *reinterpret_cast<float4*>(dst) = make_float4(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
@@ -274,8 +282,8 @@ __global__ __launch_bounds__(NW * 64) void down_skinny_kernel(const bf16_t* __re
 
 // ---------------------------------------------------------------------------------------------------------
 bool skinny_supported(const cqil_dims& d, int P, int M) {
-    return d.dtype == CQIL_BF16 && M >= 2 && M <= 8 && d.d_model % 128 == 0 && ((long long)P * d.d_ffn) % 128 == 0 &&
-           (d.head_dim / 2) % 16 == 0 && d.d_model <= 8192;
+    (void)P;
+    return d.dtype == CQIL_BF16 && M >= 2 && M <= 8 && d.d_model <= 8192;
 }
 
 template <typename K>

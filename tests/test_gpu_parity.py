@@ -48,7 +48,7 @@ def _bits(t):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("shape,P", [(TINY, 2), (ODD, 3), (MID, 1)])
+@pytest.mark.parametrize("shape,P", [(TINY, 2), (TINY, 1), (ODD, 3), (MID, 1)])
 def test_pack_group_is_a_bit_exact_index_map(shape, P, dtype):
     max_seq = 96
     d = gdims(shape, max_seq, dtype)
@@ -67,15 +67,28 @@ def test_pack_group_is_a_bit_exact_index_map(shape, P, dtype):
         return raw[off: off + n * es].numpy().view(npdt)
 
     src = [{k: _bits(v) for k, v in L.items()} for L in layers]
-    exp_qkv = np.concatenate([np.concatenate([s["wq"], s["wk"], s["wv"]], axis=0) for s in src], axis=0)
-    np.testing.assert_array_equal(region(lay.wqkv, P * 3 * dm * dm).reshape(P * 3 * dm, dm), exp_qkv)
-    exp_wo = np.stack([s["wo"] for s in src], axis=1)                       # [o][l][k]
-    np.testing.assert_array_equal(region(lay.wo, P * dm * dm).reshape(dm, P, dm), exp_wo)
-    exp_gu = np.stack([np.stack([s["wgate"].reshape(f // 16, 16, dm), s["wup"].reshape(f // 16, 16, dm)], axis=1)
-                       for s in src], axis=0)                               # [l][blk][gate|up][16][k]
-    np.testing.assert_array_equal(region(lay.wgu, P * 2 * f * dm).reshape(P, f // 16, 2, 16, dm), exp_gu)
-    exp_down = np.stack([s["wdown"] for s in src], axis=1)                  # [o][l][j]
-    np.testing.assert_array_equal(region(lay.wdown, P * dm * f).reshape(dm, P, f), exp_down)
+    V = 16 // es                      # elements per 16-byte piece
+    KB = 4 * V                        # columns per tile
+
+    def tiled(mat):
+        """[R][K] -> the tiled order: strips of 16 rows, tiles of KB columns, inside a tile [k group][row][element];
+        K is padded with zeros to whole tiles."""
+        R, K = mat.shape
+        Kp = (K + KB - 1) // KB * KB
+        pad = np.zeros((R, Kp), dtype=mat.dtype)
+        pad[:, :K] = mat
+        return pad.reshape(R // 16, 16, Kp // KB, 4, V).transpose(0, 2, 3, 1, 4).reshape(-1)
+
+    exp_qkv = np.concatenate([np.concatenate([s["wq"], s["wk"], s["wv"]], axis=0) for s in src], axis=0)   # N-concat
+    np.testing.assert_array_equal(region(lay.wqkv, P * 3 * dm * dm), tiled(exp_qkv))
+    exp_wo = np.concatenate([s["wo"] for s in src], axis=1)                                               # K-concat
+    np.testing.assert_array_equal(region(lay.wo, P * dm * dm), tiled(exp_wo))
+    exp_gu = np.concatenate([np.stack([s["wgate"].reshape(f // 16, 16, dm), s["wup"].reshape(f // 16, 16, dm)],
+                                      axis=1).reshape(2 * f, dm) for s in src], axis=0)   # 16 gate rows, 16 up rows, ...
+    np.testing.assert_array_equal(region(lay.wgu, P * 2 * f * dm), tiled(exp_gu))
+    exp_down = tiled(np.concatenate([s["wdown"] for s in src], axis=1))                                   # K-concat
+    down_elems = exp_down.size
+    np.testing.assert_array_equal(region(lay.wdown, down_elems), exp_down)
     np.testing.assert_array_equal(region(lay.g_attn, P * dm).reshape(P, dm), np.stack([s["g_attn"] for s in src]))
     np.testing.assert_array_equal(region(lay.g_ffn, P * dm).reshape(P, dm), np.stack([s["g_ffn"] for s in src]))
     # rotary table: (cos, sin)(pos * base^(-2i/d)), fp32 roundings of the double values
@@ -86,7 +99,7 @@ def test_pack_group_is_a_bit_exact_index_map(shape, P, dtype):
     np.testing.assert_allclose(table[..., 1], np.sin(phi), atol=1.2e-7, rtol=0)
     # alignment gaps between the parts are not written
     ends = [(lay.wqkv + P * 3 * dm * dm * es, lay.wo), (lay.wo + P * dm * dm * es, lay.wgu),
-            (lay.wgu + P * 2 * f * dm * es, lay.wdown), (lay.wdown + P * dm * f * es, lay.g_attn),
+            (lay.wgu + P * 2 * f * dm * es, lay.wdown), (lay.wdown + down_elems * es, lay.g_attn),
             (lay.g_attn + P * dm * es, lay.g_ffn), (lay.g_ffn + P * dm * es, lay.rope),
             (lay.rope + max_seq * half * 8, lay.total)]
     for a, b in ends:
