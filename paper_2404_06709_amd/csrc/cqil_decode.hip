@@ -22,7 +22,8 @@
 
 namespace cqil {
 
-constexpr int kU = 8;  // tiles in flight per wave
+constexpr int kU2 = 4;   // tiles in flight per strip when a wave walks two strips together
+constexpr int kU1 = 8;   // tiles in flight when a wave walks one strip
 
 // Combines the ksplit partial results of a unit.  Every wave of the workgroup calls this (it contains a
 // barrier when ksplit > 1); afterwards the wave with ks == 0 holds the totals in y[].
@@ -32,16 +33,16 @@ __device__ __forceinline__ void combine_ksplit(float (&y)[NY], int ksplit, int u
     const int lane = threadIdx.x & 63;
     if (ks > 0 && lane < 16) {
 #pragma unroll
-        for (int n = 0; n < NY; ++n) red[((ul * 8 + ks) * NY + n) * 16 + lane] = y[n];
+        for (int n = 0; n < NY; ++n) red[((ul * ksplit + ks) * NY + n) * 16 + lane] = y[n];
     }
     __syncthreads();
     if (ks == 0 && lane < 16) {
         for (int s = 1; s < ksplit; ++s)
 #pragma unroll
-            for (int n = 0; n < NY; ++n) y[n] += red[((ul * 8 + s) * NY + n) * 16 + lane];
+            for (int n = 0; n < NY; ++n) y[n] += red[((ul * ksplit + s) * NY + n) * 16 + lane];
     }
 }
-constexpr int kRedFloats = 8 * 8 * 2 * 16;  // [unit in workgroup][ks][NY <= 2][16]
+constexpr int kRedFloats = kWaves * 2 * 16;  // [unit in workgroup][ks][NY <= 2][16], units * ksplit = waves
 
 // ---------------------------------------------------------------------------------------------------------
 // 1. RMSNorm + QKV projection + rotary embedding + KV append.  grid = (unit blocks, P); a unit is the pair of
@@ -89,8 +90,8 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     if (on) {
         const size_t strip_a = ((size_t)(l * 3 + m) * d_model + (size_t)h * d_k + 16 * tp) / 16;
         const size_t strip_b = strip_a + half / 16;
-        y[0] = tile_strip_dot<T, kU>(wqkv + (strip_a * nkb + kb0) * TE, kb1 - kb0, xs + kb0 * KB);
-        y[1] = tile_strip_dot<T, kU>(wqkv + (strip_b * nkb + kb0) * TE, kb1 - kb0, xs + kb0 * KB);
+        const T* strips[2] = {wqkv + (strip_a * nkb + kb0) * TE, wqkv + (strip_b * nkb + kb0) * TE};
+        tile_strips_dot<T, 2, kU2>(strips, kb1 - kb0, xs + kb0 * KB, y);
     }
     combine_ksplit<2>(y, ksplit, ul, ks, red);
 
@@ -144,9 +145,10 @@ __global__ __launch_bounds__(kThreads) void oproj_kernel(const float* __restrict
     const int per = (nkb + ksplit - 1) / ksplit;
     const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
     float y[1] = {0.f};
-    if (on)
-        y[0] = tile_strip_dot<T, kU>(wo + ((size_t)unit * strip_tiles + (size_t)l * nkb + kb0) * TE, kb1 - kb0,
-                                     xs + kb0 * KB);
+    if (on) {
+        const T* strips[1] = {wo + ((size_t)unit * strip_tiles + (size_t)l * nkb + kb0) * TE};
+        tile_strips_dot<T, 1, kU1>(strips, kb1 - kb0, xs + kb0 * KB, y);
+    }
     combine_ksplit<1>(y, ksplit, ul, ks, red);
     if (on && ks == 0 && lane < 16) a[(size_t)l * d_model + 16 * unit + lane] = y[0];
 }
@@ -193,8 +195,8 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
     float y[2] = {0.f, 0.f};
     if (on) {
         const size_t strip_g = (size_t)l * 2 * d_ffn / 16 + 2 * (size_t)unit;  // gate strip; the up strip follows
-        y[0] = tile_strip_dot<T, kU>(wgu + (strip_g * nkb + kb0) * TE, kb1 - kb0, xs + kb0 * KB);
-        y[1] = tile_strip_dot<T, kU>(wgu + ((strip_g + 1) * nkb + kb0) * TE, kb1 - kb0, xs + kb0 * KB);
+        const T* strips[2] = {wgu + (strip_g * nkb + kb0) * TE, wgu + ((strip_g + 1) * nkb + kb0) * TE};
+        tile_strips_dot<T, 2, kU2>(strips, kb1 - kb0, xs + kb0 * KB, y);
     }
     combine_ksplit<2>(y, ksplit, ul, ks, red);
     if (on && ks == 0 && lane < 16)
@@ -209,21 +211,32 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict__ u, const T* __restrict__ wdown,
                                                          float* __restrict__ part, int K, int Kp, int d_model,
-                                                         int slice_len) {
+                                                         int slice_len, int ksplit) {
     extern __shared__ float smem[];
     constexpr int KB = tile<T>::KB, TE = tile<T>::kElems;
-    float* xs = smem;
+    float* xs = smem;                 // slice_len
+    float* red = xs + slice_len;      // kRedFloats
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int slice = blockIdx.y;
     const int k0 = slice * slice_len;
     const int len = min(slice_len, Kp - k0);  // multiple of KB
     for (int k = tid; k < len; k += kThreads) xs[k] = (k0 + k < K) ? u[k0 + k] : 0.f;
     __syncthreads();
-    const int unit = blockIdx.x * kWaves + w;
-    if (unit >= d_model / 16) return;
+    const int uw = kWaves / ksplit;
+    const int ul = w / ksplit, ks = w % ksplit;
+    const int unit = blockIdx.x * uw + ul;
+    const bool on = unit < d_model / 16;
+    const int nkb = len / KB;
+    const int per = (nkb + ksplit - 1) / ksplit;
+    const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
     const size_t strip_tiles = (size_t)Kp / KB;
-    const float y = tile_strip_dot<T, kU>(wdown + ((size_t)unit * strip_tiles + k0 / KB) * TE, len / KB, xs);
-    if (lane < 16) part[(size_t)slice * d_model + 16 * unit + lane] = y;
+    float y[1] = {0.f};
+    if (on) {
+        const T* strips[1] = {wdown + ((size_t)unit * strip_tiles + k0 / KB + kb0) * TE};
+        tile_strips_dot<T, 1, kU1>(strips, kb1 - kb0, xs + kb0 * KB, y);
+    }
+    combine_ksplit<1>(y, ksplit, ul, ks, red);
+    if (on && ks == 0 && lane < 16) part[(size_t)slice * d_model + 16 * unit + lane] = y[0];
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -246,7 +259,11 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     const int bd = s.bypass_d >= P ? P - 1 : s.bypass_d;
     constexpr int KB = tile<T>::KB;
     const int K = P * f, Kp = (K + KB - 1) / KB * KB;
-    const int ks_q = g_tune.ksplit_qkv, ks_o = g_tune.ksplit_o, ks_g = g_tune.ksplit_gu;
+    // k splits measured on 7B/13B/33B-shaped groups: narrow models want fewer, fatter workgroups
+    const bool narrow = dm <= 4096;
+    const int ks_q = g_tune.ksplit_qkv ? g_tune.ksplit_qkv : 4;
+    const int ks_o = g_tune.ksplit_o ? g_tune.ksplit_o : (narrow ? 2 : 1);
+    const int ks_g = g_tune.ksplit_gu ? g_tune.ksplit_gu : (narrow ? 2 : 4);
     const size_t lds_x = ((size_t)dm + kRedFloats + 16) * sizeof(float);
 
     // optional per-kernel timing: event i is recorded before kernel i, the last event after the last kernel
@@ -284,9 +301,13 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
                            (const T*)s.x_in, a, wgu, g_ffn, u, P, bd, dm, f, d.rms_eps, ks_g);
     }
     CQIL_MARK(4);
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(down_kernel<T>), dim3((dm / 16 + kWaves - 1) / kWaves, s.wl.n_slices),
-                       dim3(kThreads), (size_t)s.wl.down_slice * sizeof(float), st, u, wdown, dpart, K, Kp, dm,
-                       s.wl.down_slice);
+    {
+        const int ks_d = g_tune.ksplit_d ? g_tune.ksplit_d : (narrow ? 1 : 4);
+        const int units = dm / 16, uw = kWaves / ks_d;
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(down_kernel<T>), dim3((units + uw - 1) / uw, s.wl.n_slices), dim3(kThreads),
+                           ((size_t)s.wl.down_slice + kRedFloats) * sizeof(float), st, u, wdown, dpart, K, Kp, dm,
+                           s.wl.down_slice, ks_d);
+    }
     CQIL_MARK(5);
     hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 255) / 256, 1), dim3(256), 0, st, (const T*)s.x_in,
                        a, dpart, (T*)s.x_out, s.kv_len, s.advance, P, s.wl.n_slices, 1, dm, 1, 1);

@@ -103,60 +103,52 @@ __device__ __forceinline__ int xs_words(int len) { return (len + 511) & ~511; }
 // kVec columns (k group g) of row i and multiplies them with the matching input values, which sit in LDS as fp32
 // in natural order (the 16 lanes of a k group read the same address: a broadcast).  The four k groups of a row
 // are added with two cross-lane steps; every lane returns the dot product of row (lane % 16) over the n_kb tiles.
-//   strip  first tile of the range;  xs  input values of the first column of the range
+//   strip[s]  first tile of the range of strip s (NS strips advance together, NS * U tiles in flight)
+//   xs        input values of the first column of the range
 // ---------------------------------------------------------------------------------------------------------
-template <typename T, int U>
-__device__ __forceinline__ float tile_strip_dot(const T* __restrict__ strip, int n_kb, const float* xs) {
+template <typename T, int NS, int U>
+__device__ __forceinline__ void tile_strips_dot(const T* const (&strip)[NS], int n_kb, const float* xs,
+                                                float (&out)[NS]) {
     constexpr int V = tile<T>::V, KB = tile<T>::KB, TE = tile<T>::kElems;
     const int lane = threadIdx.x & 63;
-    const T* p = strip + lane * V;
     const float* xg = xs + (lane >> 4) * V;
-    float acc = 0.f;
-    int kb = 0;
-    for (; kb + U <= n_kb; kb += U) {
-        uint4 w[U];
+    float acc[NS];
 #pragma unroll
-        for (int u = 0; u < U; ++u) w[u] = load16_stream(p + (size_t)(kb + u) * TE);
+    for (int s = 0; s < NS; ++s) acc[s] = 0.f;
+    for (int kb = 0; kb < n_kb; kb += U) {
+        // NS * U tiles in flight; the conditions are wave-uniform (ragged end of the range)
+        uint4 w[NS][U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float f[V];
-            elem<T>::unpack(w[u], f);
-            const float* xp = xg + (kb + u) * KB;
+        for (int s = 0; s < NS; ++s)
 #pragma unroll
-            for (int e = 0; e < V; e += 4) {
-                const float4 xv = *reinterpret_cast<const float4*>(xp + e);
-                acc = fmaf(f[e], xv.x, acc);
-                acc = fmaf(f[e + 1], xv.y, acc);
-                acc = fmaf(f[e + 2], xv.z, acc);
-                acc = fmaf(f[e + 3], xv.w, acc);
-            }
-        }
-    }
-    if (kb < n_kb) {  // ragged end: the remaining tiles in one batch (the conditions are wave-uniform)
-        uint4 w[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (kb + u < n_kb) w[u] = load16_stream(p + (size_t)(kb + u) * TE);
+            for (int u = 0; u < U; ++u)
+                if (kb + u < n_kb) w[s][u] = load16_stream(strip[s] + (size_t)(kb + u) * TE + lane * V);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kb + u < n_kb) {
-                float f[V];
-                elem<T>::unpack(w[u], f);
+                float x[V];
                 const float* xp = xg + (kb + u) * KB;
 #pragma unroll
                 for (int e = 0; e < V; e += 4) {
                     const float4 xv = *reinterpret_cast<const float4*>(xp + e);
-                    acc = fmaf(f[e], xv.x, acc);
-                    acc = fmaf(f[e + 1], xv.y, acc);
-                    acc = fmaf(f[e + 2], xv.z, acc);
-                    acc = fmaf(f[e + 3], xv.w, acc);
+                    x[e] = xv.x; x[e + 1] = xv.y; x[e + 2] = xv.z; x[e + 3] = xv.w;
+                }
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    float f[V];
+                    elem<T>::unpack(w[s][u], f);
+#pragma unroll
+                    for (int e = 0; e < V; ++e) acc[s] = fmaf(f[e], x[e], acc[s]);
                 }
             }
         }
     }
-    acc += __shfl_xor(acc, 16, kWave);
-    acc += __shfl_xor(acc, 32, kWave);
-    return acc;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        acc[s] += __shfl_xor(acc[s], 16, kWave);
+        acc[s] += __shfl_xor(acc[s], 32, kWave);
+        out[s] = acc[s];
+    }
 }
 
 }  // namespace cqil

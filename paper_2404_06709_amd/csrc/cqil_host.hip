@@ -113,7 +113,7 @@ const char* cqil_strerror(int status) {
 
 int cqil_set_tuning(const char* key, int value) {
     if (!key) return CQIL_EINVAL;
-    const bool split_ok = value == 1 || value == 2 || value == 4 || value == 8;
+    const bool split_ok = value == 0 || value == 1 || value == 2 || value == 4 || value == 8;  // 0 = by shape
     if (!strcmp(key, "ksplit_qkv")) {
         if (!split_ok) return CQIL_EINVAL;
         g_tune.ksplit_qkv = value;
@@ -123,6 +123,9 @@ int cqil_set_tuning(const char* key, int value) {
     } else if (!strcmp(key, "ksplit_gu")) {
         if (!split_ok) return CQIL_EINVAL;
         g_tune.ksplit_gu = value;
+    } else if (!strcmp(key, "ksplit_d")) {
+        if (!split_ok) return CQIL_EINVAL;
+        g_tune.ksplit_d = value;
     } else if (!strcmp(key, "down_slice_max")) {
         if (value < 512 || value > 12288 || value % 512) return CQIL_EINVAL;
         g_tune.down_slice_max = value;

@@ -16,10 +16,10 @@ constexpr int kGuBlock = 16;        // gate/up rows are interleaved in blocks of
 constexpr int kMaxP = 16;
 
 // Launch-shape knobs of the single-token decode kernels (cqil_set_tuning): waves that share one unit of work
-// (k split: 1, 2, 4 or 8) in the QKV, O and gate/up kernels, and the longest K slice of the down projection
+// (k split: 1, 2, 4 or 8; 0 = chosen by shape) in the QKV, O, gate/up and down kernels, and the longest K slice of the down projection
 // (multiple of 512, at most 12288).
 struct Tuning {
-    int ksplit_qkv = 2, ksplit_o = 4, ksplit_gu = 1, down_slice_max = 6144;
+    int ksplit_qkv = 4, ksplit_o = 0, ksplit_gu = 0, ksplit_d = 0, down_slice_max = 8192;  // 0 = by shape
 };
 extern Tuning g_tune;
 
