@@ -14,6 +14,8 @@
 #include "cqil_dev.h"
 #include "cqil_gemv.h"
 #include "cqil_internal.h"
+#include "cqil_mfma_gemm.h"
+#include <type_traits>
 
 namespace cqil {
 
@@ -280,6 +282,18 @@ static void gemm_nt(const AT* A, const BT* B, CT* C, const float* R, int M, int 
                        lda, Kp, ldc, sA, n_step, k_step, sC);
 }
 
+// bf16 products run on the matrix cores, fp32 ones on the plain kernel above
+template <typename T, typename CT, bool ADD_R>
+static hipError_t gemm_any(const T* A, const T* W, CT* C, const float* R, int M, int N, int K, size_t lda, size_t Kp,
+                           size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step, size_t sC, hipStream_t st) {
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        return gemm_mfma<CT, ADD_R>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+    } else {
+        gemm_nt<T, T, CT, ADD_R>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+        return hipSuccess;
+    }
+}
+
 __global__ void advance_kernel(int32_t* kv_len, int B, int T) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b < B) kv_len[b] += T;
@@ -315,8 +329,9 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
 
     hipLaunchKernelGGL(HIP_KERNEL_NAME(rmsnorm_multi_kernel<T>), dim3(M), dim3(256), 0, st, x, g_attn, nrm, P, M, dm,
                        d.rms_eps);
-    gemm_nt<T, T, T, false>(nrm, wqkv, qkv, nullptr, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm,
-                            (size_t)3 * dm, 0, (size_t)3 * dm, st);
+    hipError_t ge;
+    if ((ge = gemm_any<T, T, false>(nrm, wqkv, qkv, nullptr, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm,
+                            (size_t)3 * dm, 0, (size_t)3 * dm, st)) != hipSuccess) return ge;
     hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M, P * nh), dim3(((dk / 2) + 63) / 64 * 64), 0, st,
                        qkv, rope, s.kv_len, (T*)s.kc, (T*)s.vc, P, s.T, nh, dk, d.max_seq, s.b_max);
     const int lps = dk * (int)sizeof(T) / 16;
@@ -331,11 +346,11 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
         default: return hipErrorInvalidValue;
     }
 #undef CQIL_ATTN
-    gemm_nt<T, T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, 0, (size_t)dm, Mdm, st);
+    if ((ge = gemm_any<T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, 0, (size_t)dm, Mdm, st)) != hipSuccess) return ge;
     hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(256), 0, st, x, a, g_ffn, nrm, resid, P, bd,
                        M, dm, d.rms_eps);
-    gemm_nt<T, T, T, false>(nrm, wgu, gu, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * 2 * f, P, Mdm, (size_t)2 * f, 0,
-                            (size_t)2 * f, st);
+    if ((ge = gemm_any<T, T, false>(nrm, wgu, gu, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * 2 * f, P, Mdm, (size_t)2 * f, 0,
+                            (size_t)2 * f, st)) != hipSuccess) return ge;
     {
         const size_t total = (size_t)M * P * f;
         size_t g = (total + 255) / 256;
@@ -344,7 +359,7 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     }
     {
         const size_t kt = tile<T>::KB, Kp = ((size_t)P * f + kt - 1) / kt * kt;
-        gemm_nt<T, T, T, true>(u, wdown, (T*)s.x_out, resid, M, dm, P * f, (size_t)P * f, Kp, dm, 1, 0, 0, 0, 0, st);
+        if ((ge = gemm_any<T, T, true>(u, wdown, (T*)s.x_out, resid, M, dm, P * f, (size_t)P * f, Kp, dm, 1, 0, 0, 0, 0, st)) != hipSuccess) return ge;
     }
     if (s.advance) hipLaunchKernelGGL(advance_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st, s.kv_len, s.B, s.T);
     return hipGetLastError();
