@@ -14,6 +14,7 @@
 #include "cqil_dev.h"
 #include "cqil_gemv.h"
 #include "cqil_internal.h"
+#include "cqil_mfma_attn.h"
 #include "cqil_mfma_gemm.h"
 #include <type_traits>
 
@@ -335,6 +336,23 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M, P * nh), dim3(((dk / 2) + 63) / 64 * 64), 0, st,
                        qkv, rope, s.kv_len, (T*)s.kc, (T*)s.vc, P, s.T, nh, dk, d.max_seq, s.b_max);
     const int lps = dk * (int)sizeof(T) / 16;
+    bool attn_done = false;
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        // matrix-core attention for the head sizes it is built for; positions were bounded by the caller
+        if (dk == 64 || dk == 128) {
+            const dim3 grid((s.T + kPfBQ - 1) / kPfBQ, P * s.B * nh);
+            if (dk == 64)
+                hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_prefill_mfma_kernel<64>), grid, dim3(kPfThreads), 0, st,
+                                   (const bf16_t*)qkv, (const bf16_t*)s.kc, (const bf16_t*)s.vc, s.kv_len, ctx, P, s.B, s.T,
+                                   nh, d.max_seq, s.b_max);
+            else
+                hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_prefill_mfma_kernel<128>), grid, dim3(kPfThreads), 0, st,
+                                   (const bf16_t*)qkv, (const bf16_t*)s.kc, (const bf16_t*)s.vc, s.kv_len, ctx, P, s.B, s.T,
+                                   nh, d.max_seq, s.b_max);
+            attn_done = true;
+        }
+    }
+    if (!attn_done) {
 #define CQIL_ATTN(LPS)                                                                                               \
     hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_generic_kernel<T, LPS>), dim3(M, P * nh), dim3(256), 0, st, (const T*)qkv, \
                        (const T*)s.kc, (const T*)s.vc, s.kv_len, ctx, P, M, s.T, nh, d.max_seq, s.b_max)
@@ -346,6 +364,7 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
         default: return hipErrorInvalidValue;
     }
 #undef CQIL_ATTN
+    }
     if ((ge = gemm_any<T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, 0, (size_t)dm, Mdm, st)) != hipSuccess) return ge;
     hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(256), 0, st, x, a, g_ffn, nrm, resid, P, bd,
                        M, dm, d.rms_eps);

@@ -1,0 +1,204 @@
+// Causal attention of the token-parallel (prefill) path on the matrix cores, bf16:
+//   softmax(Q K^T / sqrt(d_k)) V  (Eq.2)  for the T new tokens of every (layer, sequence, head), over the cached
+//   slots and the new tokens up to and including the query (positions kv_len[b] + t).
+//
+// Transposed formulation, so that nothing has to be re-laid out between the two products:
+//   S^T[key][query] = K Q^T     A operand = K rows (i = key), B operand = Q rows (j = query)
+//   O^T[d][query]   = V^T P^T   A operand = V^T (i = d),      B operand = P^T  (j = query)
+// With v_mfma_f32_16x16x32_bf16 the result lane j + 16 g holds rows 4g..4g+3 of column j: after the first product
+// a lane owns four consecutive keys of one query in each 16-key tile; two such tiles give it eight keys, which is
+// exactly one B-operand fragment of the second product if the instruction's k slots (g, e) are taken to mean key
+// 16 a + 4 g + e for e < 4 and 16 b + 4 g + e - 4 for e >= 4 (a, b the two tiles).  V^T is staged in LDS in that
+// same key order, so P stays in registers.  The softmax statistics of a query live in the four lanes that share
+// its column (two cross-lane steps), the running maximum / sum / output are rescaled per key tile (online softmax).
+//
+// Workgroup: 4 waves, 128 queries (32 per wave: two column tiles), key tiles of 64.  K tile and V^T tile are
+// staged in LDS as 1 KiB tiles in A-operand order.
+#pragma once
+#include "cqil_dev.h"
+
+namespace cqil {
+
+typedef __bf16 attn_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float attn_f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kPfBQ = 128, kPfBKV = 64, kPfThreads = 256;
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+
+template <int DK>
+__global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(
+    const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+    const int32_t* __restrict__ kv_len, bf16_t* __restrict__ ctx, int P, int B, int T_new, int n_heads, int max_seq,
+    int b_max) {
+    constexpr int NDB = DK / 32;  // 32-wide d blocks (k steps of the first product)
+    constexpr int NDT = DK / 16;  // 16-row d tiles (row tiles of the second product)
+    constexpr int PPK = DK / 8;   // 16-byte pieces per key row
+    constexpr int TE = 512;
+    __shared__ __align__(16) bf16_t Ks[4 * NDB * TE];   // [key tile 0..3][d block]
+    __shared__ __align__(16) bf16_t Vs[NDT * 2 * TE];   // [d tile][key block 0..1]
+
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int j = lane & 15, g = lane >> 4;
+    const int qb = gridDim.x - 1 - blockIdx.x;  // long (late) query blocks first
+    const int h = blockIdx.y % n_heads;
+    const int lb = blockIdx.y / n_heads;
+    const int b = lb % B, l = lb / B;
+    const int M = B * T_new;
+    const size_t d_model = (size_t)n_heads * DK;
+    const int S_b = kv_len[b];
+    const int q0 = qb * kPfBQ + 32 * w;
+    // keys this workgroup needs: the cache plus the new tokens up to its last query
+    int kv_end = S_b + min(qb * kPfBQ + kPfBQ, T_new);
+    if (kv_end > max_seq) kv_end = max_seq;
+    const size_t head_off = ((((size_t)l * b_max + b) * n_heads + h) * (size_t)max_seq) * DK;
+    const bf16_t* kg = kc + head_off;
+    const bf16_t* vg = vc + head_off;
+
+    // Q fragments (B operand): lane (j, g) holds Q[query j][32 ks + 8 g ..]
+    uint4 qf[2][NDB];
+    int qpos[2];
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt) {
+        const int t = q0 + 16 * jt + j;
+        qpos[jt] = (t < T_new) ? S_b + t : -1;  // -1: no such query, every key masked
+        const bf16_t* qp = qkv + ((size_t)b * T_new + min(t, T_new - 1)) * (size_t)P * 3 * d_model + (size_t)l * 3 * d_model +
+                           (size_t)h * DK + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < NDB; ++ks)
+            qf[jt][ks] = (t < T_new) ? *reinterpret_cast<const uint4*>(qp + 32 * ks) : make_uint4(0, 0, 0, 0);
+    }
+
+    attn_f32x4 acc[NDT][2];
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt) acc[dt][jt] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
+    const float scale = 1.0f / sqrtf((float)DK);
+
+    for (int key0 = 0; key0 < kv_end; key0 += kPfBKV) {
+        __syncthreads();  // the previous tile has been consumed
+        // ---- stage K (pieces copied as they are) and V^T (element-wise transposition) of 64 keys
+#pragma unroll
+        for (int q = 0; q < (kPfBKV * PPK) / kPfThreads; ++q) {
+            const int p = tid + kPfThreads * q;
+            const int key = p / PPK, c = p % PPK;
+            const int slot = key0 + key;
+            const bool ok = slot < kv_end;
+            const uint4 kv4 = ok ? *reinterpret_cast<const uint4*>(kg + (size_t)slot * DK + 8 * c) : make_uint4(0, 0, 0, 0);
+            const uint4 vv4 = ok ? *reinterpret_cast<const uint4*>(vg + (size_t)slot * DK + 8 * c) : make_uint4(0, 0, 0, 0);
+            {
+                const int kt = key >> 4, i = key & 15, db = c >> 2, gg = c & 3;
+                const int pos = gg * 16 + ((i + 4 * gg + 2 * (db & 1) + (db >> 1)) & 15);
+                *reinterpret_cast<uint4*>(Ks + (kt * NDB + db) * TE + pos * 8) = kv4;
+            }
+            {
+                const int kb2 = key >> 5, kl = key & 31;
+                const int gg = (kl & 15) >> 2, e = (kl & 3) + ((kl >> 4) << 2);  // k slot (gg, e) of this key
+                const int dt = c >> 1, i0 = (c & 1) * 8;
+                bf16_t* dst = Vs + (dt * 2 + kb2) * TE + (gg * 16 + i0) * 8 + e;
+                const uint32_t vw[4] = {vv4.x, vv4.y, vv4.z, vv4.w};
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    dst[(2 * e2) * 8] = (bf16_t)(vw[e2] & 0xffffu);
+                    dst[(2 * e2 + 1) * 8] = (bf16_t)(vw[e2] >> 16);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- S^T = K Q^T for 4 key tiles x 2 query tiles
+        attn_f32x4 s[4][2];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+#pragma unroll
+            for (int jt = 0; jt < 2; ++jt) s[it][jt] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < NDB; ++ks) {
+                const int pos = g * 16 + ((j + 4 * g + 2 * (ks & 1) + (ks >> 1)) & 15);
+                const uint4 kf = *reinterpret_cast<const uint4*>(Ks + (it * NDB + ks) * TE + pos * 8);
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt)
+                    s[it][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(attn_bf16x8, kf),
+                                                                        __builtin_bit_cast(attn_bf16x8, qf[jt][ks]), s[it][jt], 0, 0, 0);
+            }
+        }
+        // ---- mask, online softmax (per query = per column), P fragments
+        uint4 pk[2][2];  // [key block][query tile]
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt) {
+            float mloc = -INFINITY;
+#pragma unroll
+            for (int it = 0; it < 4; ++it)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int key = key0 + 16 * it + 4 * g + r;
+                    const float v = (key <= qpos[jt]) ? s[it][jt][r] * scale : -INFINITY;
+                    s[it][jt][r] = v;
+                    mloc = fmaxf(mloc, v);
+                }
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 16, kWave));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
+            const float mnew = fmaxf(mrun[jt], mloc);
+            const float corr = (mrun[jt] == -INFINITY) ? 0.f : expf(mrun[jt] - mnew);  // mnew finite whenever mrun is
+            float psum = 0.f;
+            float p[4][4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float v = s[it][jt][r];
+                    p[it][r] = (v == -INFINITY) ? 0.f : expf(v - mnew);
+                    psum += p[it][r];
+                }
+            lrun[jt] = lrun[jt] * corr + psum;
+            mrun[jt] = mnew;
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt) {
+                acc[dt][jt][0] *= corr; acc[dt][jt][1] *= corr; acc[dt][jt][2] *= corr; acc[dt][jt][3] *= corr;
+            }
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2) {
+                pk[kb2][jt].x = pack_bf16x2(p[2 * kb2][0], p[2 * kb2][1]);
+                pk[kb2][jt].y = pack_bf16x2(p[2 * kb2][2], p[2 * kb2][3]);
+                pk[kb2][jt].z = pack_bf16x2(p[2 * kb2 + 1][0], p[2 * kb2 + 1][1]);
+                pk[kb2][jt].w = pack_bf16x2(p[2 * kb2 + 1][2], p[2 * kb2 + 1][3]);
+            }
+        }
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2) {
+                const uint4 vf = *reinterpret_cast<const uint4*>(Vs + (dt * 2 + kb2) * TE + lane * 8);
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt)
+                    acc[dt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(attn_bf16x8, vf),
+                                                                          __builtin_bit_cast(attn_bf16x8, pk[kb2][jt]), acc[dt][jt], 0, 0, 0);
+            }
+    }
+
+    // ---- normalise and store: lane (j, g) holds d = 16 dt + 4 g .. + 3 of query j
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt) {
+        float lt = lrun[jt];
+        lt += __shfl_xor(lt, 16, kWave);
+        lt += __shfl_xor(lt, 32, kWave);
+        const int t = q0 + 16 * jt + j;
+        if (t >= T_new) continue;
+        const float inv = 1.0f / lt;
+        bf16_t* out = ctx + ((size_t)l * M + (size_t)b * T_new + t) * d_model + (size_t)h * DK + 4 * g;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+            uint2 o;
+            o.x = pack_bf16x2(acc[dt][jt][0] * inv, acc[dt][jt][1] * inv);
+            o.y = pack_bf16x2(acc[dt][jt][2] * inv, acc[dt][jt][3] * inv);
+            *reinterpret_cast<uint2*>(out + 16 * dt) = o;
+        }
+    }
+}
+
+}  // namespace cqil
