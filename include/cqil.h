@@ -167,12 +167,14 @@ int cqil_model_forward(cqil_model *m /* host */, const int32_t *tokens, int B, i
                        int advance_kv_len, void *hidden_out, float *logits_out, int32_t *next_token_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
-/* Launch-shape knobs of the single-token decode kernels (process-wide, host-only, not thread-safe; set them
+/* Launch-shape knobs (process-wide, host-only, not thread-safe; set them
  * before sizing workspaces).  Keys: "ksplit_qkv", "ksplit_o", "ksplit_gu", "ksplit_d" (waves that share one unit
  * of work and split its k range in the QKV / O / gate-up / down kernel: 1, 2, 4 or 8; 0 = chosen by shape),
  * "down_slice_max" (longest K slice of the down projection, multiple of 512, at
- * most 12288).  The k split and the number of K slices change the order in which partial sums are added, nothing
- * else.  Unknown key or bad value: CQIL_EINVAL. */
+ * most 12288): single-token decode kernels.  "gemm_tile" (workgroup tile of the bf16 matrix-core GEMM of the
+ * token-parallel path: 1 = 256 tokens x 256 weight rows, 2 = 128 x 256; 0 = default).  The k split
+ * and the number of K slices change the order in which partial sums are added, nothing else; the GEMM tile changes
+ * no result at all.  Unknown key or bad value: CQIL_EINVAL. */
 int cqil_set_tuning(const char *key, int value);
 
 /* Library build information (host-only). */

@@ -288,7 +288,7 @@ template <typename T, typename CT, bool ADD_R>
 static hipError_t gemm_any(const T* A, const T* W, CT* C, const float* R, int M, int N, int K, size_t lda, size_t Kp,
                            size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step, size_t sC, hipStream_t st) {
     if constexpr (std::is_same<T, bf16_t>::value) {
-        return gemm_mfma<CT, ADD_R>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+        return gemm_mfma<CT, ADD_R>(g_tune.gemm_tile, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
     } else {
         gemm_nt<T, T, CT, ADD_R>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
         return hipSuccess;

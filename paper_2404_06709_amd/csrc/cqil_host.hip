@@ -129,6 +129,9 @@ int cqil_set_tuning(const char* key, int value) {
     } else if (!strcmp(key, "down_slice_max")) {
         if (value < 512 || value > 12288 || value % 512) return CQIL_EINVAL;
         g_tune.down_slice_max = value;
+    } else if (!strcmp(key, "gemm_tile")) {
+        if (value < 0 || value > 2) return CQIL_EINVAL;
+        g_tune.gemm_tile = value;
     } else {
         return CQIL_EINVAL;
     }

@@ -4,26 +4,29 @@
 // padded width Kp; a group z (blockIdx.z) addresses a row band (N-concatenation) or a column band
 // (K-concatenation) of it.  C: row-major, bf16 or fp32; fp32 accumulation.
 //
-// Workgroup tile 256 tokens x 256 weight rows x 64 columns, 8 waves as 2 (tokens) x 4 (weight rows); a wave owns
-// 128 tokens x 64 weight rows = 8 x 4 tiles of v_mfma_f32_16x16x32_bf16 (128 accumulator registers).  The weight
-// rows are the instruction's A operand, the tokens its B operand, so a lane ends up with 4 consecutive weight
-// rows of one token: 4 consecutive elements of a C row.
-// Both operands are staged in LDS as 1 KiB tiles in operand order, so every fragment read is one contiguous
-// 16-byte-per-lane read without bank conflicts: weight tiles are copied verbatim (they are stored that way);
-// activation rows are re-tiled on the way in, with the 16-byte pieces of a tile rotated by 4 g + 2 kt so that
-// the eight pieces of one 128-byte row segment, which eight neighbouring threads write, fall into different banks.
-// Two LDS stages: the global loads of step i+1 are in flight while step i is multiplied.
+// Instruction: v_mfma_f32_32x32x16_bf16 (measured on gfx950: it sustains the full matrix rate, the 16x16x32 form
+// half of it).  The weight rows are its A operand (lane i + 32 gg holds row i, columns 8 gg .. 8 gg + 7 of a
+// 16-column slab), the tokens its B operand, so a lane ends up with groups of 4 consecutive weight rows of one
+// token: 4 consecutive elements of a C row.
+// A workgroup of WM x WN waves owns 128 WM tokens x 64 WN weight rows; a wave owns 128 tokens x 64 weight rows =
+// 4 x 2 instruction tiles (128 accumulator registers).
+// Weights never touch LDS: the packed layout stores every 16-row x 32-column tile in [column group][row] order,
+// so the fragment of 32 rows x 16 columns is four contiguous 256-byte runs of two vertically adjacent tiles,
+// which a wave reads straight from global memory, one 32-column slab ahead of use.
+// Activations are staged in LDS as 1 KiB tiles of 32 tokens x 16 columns in operand order ([gg][token], 16-byte
+// pieces), re-tiled on the way in; the piece of token j and piece index c of the 64-column step goes to slot
+// (j + c) mod 32 of its half tile, so that the eight pieces of one 128-byte row segment, which eight neighbouring
+// threads write, fall into different banks; every fragment read is one contiguous 16-byte-per-lane read.
+// Two LDS stages of 64 columns: the global loads of step i+1 are in flight while step i is multiplied.
+// All loads are unconditional with clamped addresses (no divergent branches in the loop): rows or strips outside
+// the problem are computed from clamped data and never stored; columns beyond K are zeroed on the activation side.
 #pragma once
 #include "cqil_dev.h"
 
 namespace cqil {
 
 typedef __bf16 gemm_bf16x8 __attribute__((ext_vector_type(8)));
-typedef float gemm_f32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kGemmBM = 256, kGemmBN = 256, kGemmBK = 64, kGemmThreads = 512;
-constexpr int kGemmStageElems = (kGemmBM + kGemmBN) * kGemmBK;         // bf16 elements per stage
-constexpr size_t kGemmLdsBytes = 2 * (size_t)kGemmStageElems * 2;      // two stages
+typedef float gemm_f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ void gemm_store4(bf16_t* p, const float (&v)[4]) {
     uint2 o;
@@ -35,132 +38,186 @@ __device__ __forceinline__ void gemm_store4(float* p, const float (&v)[4]) {
     *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
 }
 
-// N, K: logical sizes of this group's product; N % 4 == 0.  n_strip0 / k_tile0: first 16-row strip / first
-// 32-column tile of the group inside W.  R (ADD_R): fp32 [M][N] added to the result.
-template <typename CT, bool ADD_R>
-__global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(
+// N, K: logical sizes of this group's product; N % 4 == 0, K % 8 == 0, M >= 1.  strip_step / ktile_step: group
+// strides in 16-row strips / 32-column tiles inside W.  R (ADD_R): fp32 [M][N] added to the result.
+template <typename CT, bool ADD_R, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, CT* __restrict__ C, const float* __restrict__ R, int M,
     int N, int K, size_t lda, size_t Kp, size_t ldc, size_t sA, size_t strip_step, size_t ktile_step, size_t sC) {
+    constexpr int BM = 128 * WM, BN = 64 * WN, NT = 64 * WM * WN;
+    constexpr int TE = 512;            // elements per tile
+    constexpr int STAGE = BM * 64;     // activation elements per LDS stage
+    constexpr int APT = BM * 8 / NT;   // activation pieces per thread and step
     extern __shared__ __align__(16) unsigned char gemm_smem[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(gemm_smem);
-    constexpr int TE = 512;  // elements per tile
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-    const int wm = w >> 2, wn = w & 3;
+    const int wm = w / WN, wn = w % WN;
     const int z = blockIdx.z;
     A += (size_t)z * sA;
     C += (size_t)z * sC;
-    const size_t n_strip0 = (size_t)z * strip_step, k_tile0 = (size_t)z * ktile_step;
-    const int m0 = blockIdx.y * kGemmBM, n0 = blockIdx.x * kGemmBN;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const size_t w_tiles_per_strip = Kp / 32;
-    const int n_strips = N / 16 + ((N % 16) ? 1 : 0);   // strips of this group that exist (N % 16 == 0 in practice)
+    const int n_strips = (N + 15) / 16;
     const int n_ktiles = (K + 31) / 32;
     const int n_steps = (n_ktiles + 1) / 2;
 
-    // ---- global -> register staging of one step (4 weight pieces, 4 activation pieces per thread)
-    uint4 wreg[4], areg[4];
-    auto load_step = [&](int step) {
-        const int kt0 = 2 * step;
+    // weight fragments: rows 32 s .. 32 s + 31 of the wave's 64 = strips 4 wn + 2 s + (i >> 4); lane (i, gg) reads
+    // piece (2 hf + gg) * 16 + (i & 15) of tile kt for the 16-column slab k16 = 2 kt + hf: 256 elements per slab
+    const int fi = lane & 31, fgg = lane >> 5;
+    const int n_k16 = 2 * n_ktiles;
+    const bf16_t* wp[2];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int tile_idx = w + 8 * q;              // 0..31 = strip_local * 2 + kt
-            const int strip = n0 / 16 + (tile_idx >> 1);
-            const int kt = kt0 + (tile_idx & 1);
-            wreg[q] = (strip < n_strips && kt < n_ktiles)
-                          ? *reinterpret_cast<const uint4*>(W + ((n_strip0 + strip) * w_tiles_per_strip + k_tile0 + kt) * TE + lane * 8)
-                          : make_uint4(0, 0, 0, 0);
-        }
+    for (int s = 0; s < 2; ++s) {
+        const int strip = min(n0 / 16 + 4 * wn + 2 * s + (fi >> 4), n_strips - 1);
+        wp[s] = W + (((size_t)z * strip_step + strip) * w_tiles_per_strip + (size_t)z * ktile_step) * TE +
+                (fgg * 16 + (fi & 15)) * 8;
+    }
+    uint4 wf[4][2];  // [slab of the step][s]
+    auto load_w = [&](int b, int k16) {
+        const size_t off = (size_t)min(k16, n_k16 - 1) * 256;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int row = (tid >> 3) + 64 * q;         // 0..255
-            const int c = tid & 7;                       // 16-byte piece along k
-            const int m = m0 + row, k = 64 * step + 8 * c;
-            areg[q] = (m < M && k < K) ? *reinterpret_cast<const uint4*>(A + (size_t)m * lda + k) : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto store_step = [&](int buf) {
-        bf16_t* ws = lds + (size_t)buf * kGemmStageElems;
-        bf16_t* as = ws + kGemmBN * kGemmBK;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4*>(ws + (w + 8 * q) * TE + lane * 8) = wreg[q];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int row = (tid >> 3) + 64 * q, c = tid & 7;
-            const int ts = row >> 4, j = row & 15, kt = c >> 2, g = c & 3;
-            const int pos = g * 16 + ((j + 4 * g + 2 * kt) & 15);
-            *reinterpret_cast<uint4*>(as + (ts * 2 + kt) * TE + pos * 8) = areg[q];
-        }
+        for (int s = 0; s < 2; ++s) wf[b][s] = *reinterpret_cast<const uint4*>(wp[s] + off);
     };
 
-    gemm_f32x4 acc[8][4];
+    // activation pieces: thread -> (row, 16-byte piece c) of the 64-column step, APT rows NT/8 apart
+    const int c = tid & 7;
+    const bf16_t* ap[APT];
+    int a_lds[APT];
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
+    for (int q = 0; q < APT; ++q) {
+        const int row = (tid >> 3) + (NT / 8) * q;
+        ap[q] = A + (size_t)min(m0 + row, M - 1) * lda;
+        const int ts = row >> 5, j = row & 31, k16 = c >> 1, gg = c & 1;
+        a_lds[q] = (ts * 4 + k16) * TE + (gg * 32 + ((j + c) & 31)) * 8;
+    }
+    uint4 areg[APT];
+    uint32_t a_keep = 0;  // all ones if the loaded columns exist, else zero (applied when the pieces go to LDS)
+    auto load_a = [&](int step) {
+        const int k = 64 * step + 8 * c;
+        const bool ok = k < K;
+        const int kc = ok ? k : K - 8;
+        a_keep = ok ? 0xffffffffu : 0u;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) acc[t][s] = gemm_f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < APT; ++q) areg[q] = *reinterpret_cast<const uint4*>(ap[q] + kc);
+    };
+    auto store_a = [&](bf16_t* as) {
+#pragma unroll
+        for (int q = 0; q < APT; ++q)
+            *reinterpret_cast<uint4*>(as + a_lds[q]) =
+                make_uint4(areg[q].x & a_keep, areg[q].y & a_keep, areg[q].z & a_keep, areg[q].w & a_keep);
+    };
 
-    const int j = lane & 15, g = lane >> 4;
-    load_step(0);
-    store_step(0);
+    gemm_f32x16 acc[4][2];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][s][r] = 0.f;
+
+    // activation fragment of token tile t, slab k16 of the step: tile (4 wm + t) * 4 + k16, slot (j + 2 k16 + gg) mod 32
+    int frag[4];
+#pragma unroll
+    for (int k16 = 0; k16 < 4; ++k16) frag[k16] = (4 * wm * 4 + k16) * TE + (fgg * 32 + ((fi + 2 * k16 + fgg) & 31)) * 8;
+    auto read_af = [&](uint4(&af)[4], const bf16_t* as, int k16) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) af[t] = *reinterpret_cast<const uint4*>(as + frag[k16] + t * 4 * TE);
+    };
+    auto mma = [&](const uint4(&af)[4], int b) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                acc[t][s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(gemm_bf16x8, wf[b][s]),
+                                                                    __builtin_bit_cast(gemm_bf16x8, af[t]), acc[t][s], 0, 0, 0);
+    };
+
+    // Software pipeline, one slab (16 columns, 8 instructions) per stage: the fragments of slab b+1 are read
+    // from LDS before the instructions of slab b are issued, the weights of a slab are fetched a whole step ahead,
+    // and the next step's activations are written to the other LDS stage before the third slab's instructions, so
+    // that the single barrier of a step is passed while those are in the pipe.  The scheduling barriers keep the
+    // compiler from undoing the order.
+    uint4 afa[4], afb[4];
+    load_a(0);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) load_w(b, b);
+    store_a(lds);
     __syncthreads();
+    read_af(afa, lds, 0);
     for (int step = 0; step < n_steps; ++step) {
-        const int buf = step & 1;
-        if (step + 1 < n_steps) load_step(step + 1);
-        const bf16_t* ws = lds + (size_t)buf * kGemmStageElems;
-        const bf16_t* as = ws + kGemmBN * kGemmBK;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            uint4 wf[4], af[8];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) wf[s] = *reinterpret_cast<const uint4*>(ws + ((4 * wn + s) * 2 + kt) * TE + lane * 8);
-            const int pos = g * 16 + ((j + 4 * g + 2 * kt) & 15);
-#pragma unroll
-            for (int t = 0; t < 8; ++t) af[t] = *reinterpret_cast<const uint4*>(as + ((8 * wm + t) * 2 + kt) * TE + pos * 8);
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-#pragma unroll
-                for (int s = 0; s < 4; ++s)
-                    acc[t][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(gemm_bf16x8, wf[s]),
-                                                                        __builtin_bit_cast(gemm_bf16x8, af[t]), acc[t][s], 0, 0, 0);
-        }
-        if (step + 1 < n_steps) store_step(buf ^ 1);
+        bf16_t* cur = lds + (step & 1) * STAGE;
+        bf16_t* nxt = lds + ((step & 1) ^ 1) * STAGE;
+        const int k16n = 4 * (step + 1);
+        load_a(step + 1);  // beyond the last step: zeros, stored to the idle stage and never used
+        read_af(afb, cur, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(afa, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(0, k16n);
+        read_af(afa, cur, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(afb, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(1, k16n + 1);
+        read_af(afb, cur, 3);
+        store_a(nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(afa, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(2, k16n + 2);
         __syncthreads();
+        read_af(afa, nxt, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(afb, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(3, k16n + 3);
     }
 
-    // ---- epilogue: lane (j, g) holds weight rows 4g .. 4g+3 of token j of every 16x16 tile
+    // ---- epilogue: lane (j, h) holds, in registers 4 q .. 4 q + 3, weight rows 8 q + 4 h .. + 3 of token j
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const int m = m0 + 128 * wm + 16 * t + j;
+    for (int t = 0; t < 4; ++t) {
+        const int m = m0 + 128 * wm + 32 * t + fi;
         if (m >= M) continue;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int n = n0 + 64 * wn + 16 * s + 4 * g;
-            if (n >= N) continue;
-            float v[4] = {acc[t][s][0], acc[t][s][1], acc[t][s][2], acc[t][s][3]};
-            if (ADD_R) {
-                const float4 r = *reinterpret_cast<const float4*>(R + (size_t)m * N + n);
-                v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w;
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + 64 * wn + 32 * s + 8 * q + 4 * fgg;
+                if (n >= N) continue;
+                float v[4] = {acc[t][s][4 * q], acc[t][s][4 * q + 1], acc[t][s][4 * q + 2], acc[t][s][4 * q + 3]};
+                if (ADD_R) {
+                    const float4 r = *reinterpret_cast<const float4*>(R + (size_t)m * N + n);
+                    v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w;
+                }
+                gemm_store4(C + (size_t)m * ldc + n, v);
             }
-            gemm_store4(C + (size_t)m * ldc + n, v);
-        }
     }
 }
 
 // Same argument convention as the plain kernel of the token-parallel path: n_step / k_step are the group strides
 // in weight rows / columns (multiples of 16 / 32).
-template <typename CT, bool ADD_R>
-static hipError_t gemm_mfma(const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K, size_t lda,
-                            size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step, size_t sC,
-                            hipStream_t st) {
-    static bool allowed = false;
-    if (!allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_kernel<CT, ADD_R>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
-        if (e != hipSuccess) return e;
-        allowed = true;
-    }
-    dim3 grid((N + kGemmBN - 1) / kGemmBN, (M + kGemmBM - 1) / kGemmBM, groups);
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, ADD_R>), grid, dim3(kGemmThreads), kGemmLdsBytes, st, A, W, C,
-                       R, M, N, K, lda, Kp, ldc, sA, n_step / 16, k_step / 32, sC);
+template <typename CT, bool ADD_R, int WM, int WN>
+static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K,
+                                   size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step,
+                                   size_t k_step, size_t sC, hipStream_t st) {
+    constexpr int BM = 128 * WM, BN = 64 * WN;
+    constexpr size_t lds_bytes = 2 * (size_t)BM * 64 * 2;
+    dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, groups);
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, ADD_R, WM, WN>), grid, dim3(64 * WM * WN), lds_bytes, st, A,
+                       W, C, R, M, N, K, lda, Kp, ldc, sA, n_step / 16, k_step / 32, sC);
     return hipSuccess;
+}
+
+// tile: 1 = 256 tokens x 256 rows (8 waves), 2 = 128 x 256 (4 waves); 0 = default
+template <typename CT, bool ADD_R>
+static hipError_t gemm_mfma(int tile_sel, const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K,
+                            size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step,
+                            size_t sC, hipStream_t st) {
+    if (M < 1 || (N & 3) || (K & 7) || K < 8) return hipErrorInvalidValue;
+    switch (tile_sel) {
+        case 2: return gemm_mfma_launch<CT, ADD_R, 1, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+        default: return gemm_mfma_launch<CT, ADD_R, 2, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+    }
 }
 
 }  // namespace cqil
