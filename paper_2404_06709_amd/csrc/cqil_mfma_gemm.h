@@ -43,7 +43,8 @@ __device__ __forceinline__ void gemm_store4(float* p, const float (&v)[4]) {
 template <typename CT, bool ADD_R, int WM, int WN>
 __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, CT* __restrict__ C, const float* __restrict__ R, int M,
-    int N, int K, size_t lda, size_t Kp, size_t ldc, size_t sA, size_t strip_step, size_t ktile_step, size_t sC) {
+    int N, int K, size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t strip_step, size_t ktile_step,
+    size_t sC) {
     constexpr int BM = 128 * WM, BN = 64 * WN, NT = 64 * WM * WN;
     constexpr int TE = 512;            // elements per tile
     constexpr int STAGE = BM * 64;     // activation elements per LDS stage
@@ -52,10 +53,20 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     bf16_t* lds = reinterpret_cast<bf16_t*>(gemm_smem);
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int wm = w / WN, wn = w % WN;
-    const int z = blockIdx.z;
+    // Workgroup -> tile.  The hardware deals consecutive workgroups of the 1-D grid to the 8 XCDs in turn, and
+    // each XCD has its own L2: the workgroups that run together on one XCD (every 8th) are given a compact
+    // block of SM x SN tiles, so that they share SM activation bands and SN weight bands in that L2.
+    constexpr int SN = 8, SM = (WM * WN == 8) ? 4 : 8, ST = SM * SN;
+    const int nx = (N + BN - 1) / BN, ny = (M + BM - 1) / BM;
+    const int snx = (nx + SN - 1) / SN, sny = (ny + SM - 1) / SM;
+    const int L = blockIdx.x, idx = L >> 3;
+    const int S = (idx / ST) * 8 + (L & 7), t = idx % ST;
+    const int z = S / (snx * sny), s2 = S % (snx * sny);
+    const int nt = (s2 % snx) * SN + t % SN, mt = (s2 / snx) * SM + t / SN;
+    if (z >= groups || nt >= nx || mt >= ny) return;  // padding of the grid (uniform for the workgroup)
     A += (size_t)z * sA;
     C += (size_t)z * sC;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int m0 = mt * BM, n0 = nt * BN;
     const size_t w_tiles_per_strip = Kp / 32;
     const int n_strips = (N + 15) / 16;
     const int n_ktiles = (K + 31) / 32;
@@ -202,9 +213,13 @@ static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, cons
                                    size_t k_step, size_t sC, hipStream_t st) {
     constexpr int BM = 128 * WM, BN = 64 * WN;
     constexpr size_t lds_bytes = 2 * (size_t)BM * 64 * 2;
-    dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, groups);
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, ADD_R, WM, WN>), grid, dim3(64 * WM * WN), lds_bytes, st, A,
-                       W, C, R, M, N, K, lda, Kp, ldc, sA, n_step / 16, k_step / 32, sC);
+    constexpr int SN = 8, SM = (WM * WN == 8) ? 4 : 8;
+    const int nx = (N + BN - 1) / BN, ny = (M + BM - 1) / BM;
+    const long supers = (long)groups * ((nx + SN - 1) / SN) * ((ny + SM - 1) / SM);
+    const long wgs = (supers + 7) / 8 * 8 * SM * SN;
+    if (wgs > 0x7fffffffL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, ADD_R, WM, WN>), dim3((unsigned)wgs), dim3(64 * WM * WN),
+                       lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16, k_step / 32, sC);
     return hipSuccess;
 }
 
