@@ -13,7 +13,9 @@
 // its column (two cross-lane steps), the running maximum / sum / output are rescaled per key tile (online softmax).
 //
 // Workgroup: 4 waves, 128 queries (32 per wave: two column tiles), key tiles of 64.  K tile and V^T tile are
-// staged in LDS as 1 KiB tiles in A-operand order.
+// staged in LDS as 1 KiB tiles in A-operand order; the next tile's K and V rows are fetched into registers while
+// the current one is multiplied.  V is transposed in registers: a thread fetches 4 values of d for the 8 keys of
+// one operand piece and writes 4 complete 16-byte pieces (no sub-word LDS writes).
 #pragma once
 #include "cqil_dev.h"
 
@@ -29,7 +31,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 }
 
 template <int DK>
-__global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(
+__global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
     const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
     const int32_t* __restrict__ kv_len, bf16_t* __restrict__ ctx, int P, int B, int T_new, int n_heads, int max_seq,
     int b_max) {
@@ -37,6 +39,10 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(
     constexpr int NDT = DK / 16;  // 16-row d tiles (row tiles of the second product)
     constexpr int PPK = DK / 8;   // 16-byte pieces per key row
     constexpr int TE = 512;
+    constexpr int KPT = (kPfBKV * PPK) / kPfThreads;        // K pieces per thread and tile
+    constexpr int NVG = (kPfBKV / 8) * (DK / 4);            // V groups (8 keys x 4 d) of a tile
+    constexpr int VG = (NVG + kPfThreads - 1) / kPfThreads;  // per thread (the last round may be partial: whole waves)
+    static_assert(KPT >= 1 && NVG % 64 == 0, "tile too small for the workgroup");
     __shared__ __align__(16) bf16_t Ks[4 * NDB * TE];   // [key tile 0..3][d block]
     __shared__ __align__(16) bf16_t Vs[NDT * 2 * TE];   // [d tile][key block 0..1]
 
@@ -53,6 +59,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(
     // keys this workgroup needs: the cache plus the new tokens up to its last query
     int kv_end = S_b + min(qb * kPfBQ + kPfBQ, T_new);
     if (kv_end > max_seq) kv_end = max_seq;
+    if (kv_end < 1) return;  // a negative kv_len: nothing to read (whole workgroup)
     const size_t head_off = ((((size_t)l * b_max + b) * n_heads + h) * (size_t)max_seq) * DK;
     const bf16_t* kg = kc + head_off;
     const bf16_t* vg = vc + head_off;
@@ -71,44 +78,85 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(
             qf[jt][ks] = (t < T_new) ? *reinterpret_cast<const uint4*>(qp + 32 * ks) : make_uint4(0, 0, 0, 0);
     }
 
+    // ---- staging roles.  K: piece p = tid + 256 q -> key p / PPK, piece c = p % PPK of the row.
+    // V: group v = tid + 256 q -> d quad dq = v % (DK/4), key group kgp = v / (DK/4): the 8 keys of operand piece
+    // (kb2 = kgp >> 2, g = kgp & 3), i.e. key 32 kb2 + 16 (e >> 2) + 4 g + (e & 3) for slot e.
+    uint4 kreg[KPT];
+    uint2 vreg[VG][8];
+    auto fetch = [&](int key0) {
+#pragma unroll
+        for (int q = 0; q < KPT; ++q) {
+            const int p = tid + kPfThreads * q;
+            const int slot = min(key0 + p / PPK, kv_end - 1);  // rows past the end: any row, they are masked
+            kreg[q] = *reinterpret_cast<const uint4*>(kg + (size_t)slot * DK + 8 * (p % PPK));
+        }
+#pragma unroll
+        for (int q = 0; q < VG; ++q) {
+            const int v = tid + kPfThreads * q;
+            if (v >= NVG) break;
+            const int dq = v % (DK / 4), kgp = v / (DK / 4);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int key = 32 * (kgp >> 2) + 16 * (e >> 2) + 4 * (kgp & 3) + (e & 3);
+                const int slot = key0 + key;
+                // V rows past the end must be zero: their probabilities are zero, but 0 * garbage may be NaN
+                vreg[q][e] = (slot < kv_end) ? *reinterpret_cast<const uint2*>(vg + (size_t)slot * DK + 4 * dq) : make_uint2(0, 0);
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int q = 0; q < KPT; ++q) {
+            const int p = tid + kPfThreads * q;
+            const int key = p / PPK, c = p % PPK;
+            const int kt = key >> 4, i = key & 15, db = c >> 2, gg = c & 3;
+            const int pos = gg * 16 + ((i + 4 * gg + 2 * (db & 1) + (db >> 1)) & 15);
+            *reinterpret_cast<uint4*>(Ks + (kt * NDB + db) * TE + pos * 8) = kreg[q];
+        }
+#pragma unroll
+        for (int q = 0; q < VG; ++q) {
+            const int v = tid + kPfThreads * q;
+            if (v >= NVG) break;
+            const int dq = v % (DK / 4), kgp = v / (DK / 4);
+            const int kb2 = kgp >> 2, gg = kgp & 3, dt = dq >> 2;
+#pragma unroll
+            for (int dd = 0; dd < 4; ++dd) {
+                // piece of d = 4 dq + dd: the 8 keys' values, two per dword
+                const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
+                uint4 o;
+                if (dd < 2) {
+                    o.x = __builtin_amdgcn_perm(vreg[q][1].x, vreg[q][0].x, sel);
+                    o.y = __builtin_amdgcn_perm(vreg[q][3].x, vreg[q][2].x, sel);
+                    o.z = __builtin_amdgcn_perm(vreg[q][5].x, vreg[q][4].x, sel);
+                    o.w = __builtin_amdgcn_perm(vreg[q][7].x, vreg[q][6].x, sel);
+                } else {
+                    o.x = __builtin_amdgcn_perm(vreg[q][1].y, vreg[q][0].y, sel);
+                    o.y = __builtin_amdgcn_perm(vreg[q][3].y, vreg[q][2].y, sel);
+                    o.z = __builtin_amdgcn_perm(vreg[q][5].y, vreg[q][4].y, sel);
+                    o.w = __builtin_amdgcn_perm(vreg[q][7].y, vreg[q][6].y, sel);
+                }
+                const int i = 4 * (dq & 3) + dd;
+                // rotate the pieces of a tile by its d tile index: the 16 lanes written together differ in
+                // (dq & 3, dt) and then fall into 16 different bank groups
+                *reinterpret_cast<uint4*>(Vs + (dt * 2 + kb2) * TE + (gg * 16 + ((i + dt) & 15)) * 8) = o;
+            }
+        }
+    };
+
     attn_f32x4 acc[NDT][2];
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
         for (int jt = 0; jt < 2; ++jt) acc[dt][jt] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
     float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
-    const float scale = 1.0f / sqrtf((float)DK);
+    const float scale2 = 1.4426950408889634f / sqrtf((float)DK);  // scores in units of log 2: exp(x) = exp2(x log2 e)
 
+    fetch(0);
     for (int key0 = 0; key0 < kv_end; key0 += kPfBKV) {
         __syncthreads();  // the previous tile has been consumed
-        // ---- stage K (pieces copied as they are) and V^T (element-wise transposition) of 64 keys
-#pragma unroll
-        for (int q = 0; q < (kPfBKV * PPK) / kPfThreads; ++q) {
-            const int p = tid + kPfThreads * q;
-            const int key = p / PPK, c = p % PPK;
-            const int slot = key0 + key;
-            const bool ok = slot < kv_end;
-            const uint4 kv4 = ok ? *reinterpret_cast<const uint4*>(kg + (size_t)slot * DK + 8 * c) : make_uint4(0, 0, 0, 0);
-            const uint4 vv4 = ok ? *reinterpret_cast<const uint4*>(vg + (size_t)slot * DK + 8 * c) : make_uint4(0, 0, 0, 0);
-            {
-                const int kt = key >> 4, i = key & 15, db = c >> 2, gg = c & 3;
-                const int pos = gg * 16 + ((i + 4 * gg + 2 * (db & 1) + (db >> 1)) & 15);
-                *reinterpret_cast<uint4*>(Ks + (kt * NDB + db) * TE + pos * 8) = kv4;
-            }
-            {
-                const int kb2 = key >> 5, kl = key & 31;
-                const int gg = (kl & 15) >> 2, e = (kl & 3) + ((kl >> 4) << 2);  // k slot (gg, e) of this key
-                const int dt = c >> 1, i0 = (c & 1) * 8;
-                bf16_t* dst = Vs + (dt * 2 + kb2) * TE + (gg * 16 + i0) * 8 + e;
-                const uint32_t vw[4] = {vv4.x, vv4.y, vv4.z, vv4.w};
-#pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2) {
-                    dst[(2 * e2) * 8] = (bf16_t)(vw[e2] & 0xffffu);
-                    dst[(2 * e2 + 1) * 8] = (bf16_t)(vw[e2] >> 16);
-                }
-            }
-        }
+        stage();
         __syncthreads();
+        if (key0 + kPfBKV < kv_end) fetch(key0 + kPfBKV);  // in flight during the products below
 
         // ---- S^T = K Q^T for 4 key tiles x 2 query tiles
         attn_f32x4 s[4][2];
@@ -136,22 +184,23 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int key = key0 + 16 * it + 4 * g + r;
-                    const float v = (key <= qpos[jt]) ? s[it][jt][r] * scale : -INFINITY;
+                    const float v = (key <= qpos[jt]) ? s[it][jt][r] * scale2 : -INFINITY;
                     s[it][jt][r] = v;
                     mloc = fmaxf(mloc, v);
                 }
             mloc = fmaxf(mloc, __shfl_xor(mloc, 16, kWave));
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
             const float mnew = fmaxf(mrun[jt], mloc);
-            const float corr = (mrun[jt] == -INFINITY) ? 0.f : expf(mrun[jt] - mnew);  // mnew finite whenever mrun is
+            // exp2(-inf) = 0 covers the first tile and masked keys; a query with no key yet keeps mnew = -inf
+            const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+            const float corr = __builtin_amdgcn_exp2f(mrun[jt] - msafe);
             float psum = 0.f;
             float p[4][4];
 #pragma unroll
             for (int it = 0; it < 4; ++it)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float v = s[it][jt][r];
-                    p[it][r] = (v == -INFINITY) ? 0.f : expf(v - mnew);
+                    p[it][r] = __builtin_amdgcn_exp2f(s[it][jt][r] - msafe);
                     psum += p[it][r];
                 }
             lrun[jt] = lrun[jt] * corr + psum;
@@ -173,7 +222,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(
         for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
             for (int kb2 = 0; kb2 < 2; ++kb2) {
-                const uint4 vf = *reinterpret_cast<const uint4*>(Vs + (dt * 2 + kb2) * TE + lane * 8);
+                const uint4 vf = *reinterpret_cast<const uint4*>(Vs + (dt * 2 + kb2) * TE + (g * 16 + ((j + dt) & 15)) * 8);
 #pragma unroll
                 for (int jt = 0; jt < 2; ++jt)
                     acc[dt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(attn_bf16x8, vf),
