@@ -3,7 +3,7 @@
 
 Workload (the one the headline metric is quoted on): ONE LLaMA-33B-shaped group of P=4 input-aligned layers,
 bf16, batch 1, single-token decode steps with the KV cache growing from 512 to 640 tokens (the decode phase of
-the full-model configuration), bypass distance 1.  A "step" is one whole group step: all five kernels.
+the full-model configuration), bypass distance 1.  A "step" is one whole group step: all six kernels (QKV+rotary+append, attention, O, gate/up, down, merge).
 
 Prints one JSON line: the step latency (the metric), the achieved fraction of the HBM roofline for the dominant
 kernel measured live with HIP events, and the CPU oracle timed on a bounded sample of the same workload.
@@ -25,7 +25,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
 # what the same counters read for a plain copy kernel (profiles/decode_step_33b_P4_B1_hbm_traffic.md).  Only valid
 # for the workload it was measured on; other workloads report null.
-MEASURED_TRAFFIC = {("33b", 4, "gateup"): 1_909_988_841}
+MEASURED_TRAFFIC = {("33b", 4, "gateup"): 1_909_943_295}
 
 
 def kernel_bytes(shape, P, lens, es=2):
@@ -43,6 +43,47 @@ def kernel_bytes(shape, P, lens, es=2):
     }
 
 
+MFMA_PEAK_TFLOPS = 2500.0
+
+
+def prefill(args, cq, rt, synth, torch) -> int:
+    """One token-parallel group step (prefill of B sequences of T tokens onto empty caches), timed as a whole."""
+    shape = synth.SHAPES[args.shape]
+    P, B, T = args.P, args.batch, args.prefill
+    dtype = torch.bfloat16
+    dims = cq.make_dims(shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, T, dtype)
+    layers = synth.make_layers(P, shape, dtype, seed=1004, device="cuda")
+    group = rt.Group(dims, layers, b_max=B, device="cuda")
+    x = synth.normal((B, T, shape.d_model), 1.0, dtype, synth.generator(3004, "cuda"))
+    y = torch.empty_like(x)
+    steps, warmup = min(args.steps, 20), min(args.warmup, 5)
+    group.set_kv_len([0] * B)
+    for _ in range(warmup):
+        group.forward(x, args.bypass, advance=False, out=y)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        group.forward(x, args.bypass, advance=False, out=y)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    M, dm, f = B * T, shape.d_model, shape.d_ffn
+    # algorithmic flops: every projection once, causal attention without the masked half
+    flops = P * (2 * M * (4 * dm * dm + 3 * dm * f) + B * 2 * T * (T + 1) * dm)
+    tf = flops / dt / 1e12
+    print(json.dumps({
+        "metric": "prefill_tflops_per_P_layer_group", "value": round(tf, 1), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(dt * 1e3, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"llama{args.shape}_shape_group_P{P}_prefill_B{B}_T{T}", "d_model": dm,
+                   "n_heads": shape.n_heads, "d_ffn": f, "P": P, "bypass_d": args.bypass, "batch": B, "T": T},
+        "tokens_per_s": round(M / dt, 1), "flops_per_step": flops,
+        "roofline": {"bound": "mfma", "kernel": "whole group step", "achieved": round(tf, 1),
+                     "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_PEAK_TFLOPS, 4),
+                     "traffic": None},
+    }))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,6 +96,9 @@ def main() -> int:
     ap.add_argument("--kv-span", type=int, default=128)
     ap.add_argument("--batch", type=int, default=1, help="sequences per step (bf16 small-batch path for 2..8)")
     ap.add_argument("--kv-hi", type=int, default=0, help="with --batch: lengths uniform in [kv-start, kv-hi]")
+    ap.add_argument("--prefill", type=int, default=0, metavar="T",
+                    help="time one token-parallel group step over --batch sequences of T new tokens (empty caches) "
+                         "instead of decode steps; reports TFLOP/s against the bf16 matrix-core peak")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=4)
@@ -75,6 +119,8 @@ def main() -> int:
         return 2
     cq.lib()  # fails loudly if libcqil.so has not been built
     dev = "cuda"
+    if args.prefill > 0:
+        return prefill(args, cq, rt, synth, torch)
     shape = synth.SHAPES[args.shape]
     P, d_byp = args.P, args.bypass
     dtype = torch.bfloat16

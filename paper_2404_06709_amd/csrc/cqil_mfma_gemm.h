@@ -229,10 +229,10 @@ static hipError_t gemm_mfma(int tile_sel, const bf16_t* A, const bf16_t* W, CT* 
                             size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step,
                             size_t sC, hipStream_t st) {
     if (M < 1 || (N & 3) || (K & 7) || K < 8) return hipErrorInvalidValue;
-    switch (tile_sel) {
-        case 2: return gemm_mfma_launch<CT, ADD_R, 1, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
-        default: return gemm_mfma_launch<CT, ADD_R, 2, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
-    }
+    // default: 128 x 256 (two workgroups per CU overlap each other's barriers and load latency)
+    if (tile_sel == 1)
+        return gemm_mfma_launch<CT, ADD_R, 2, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+    return gemm_mfma_launch<CT, ADD_R, 1, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
 }
 
 }  // namespace cqil
