@@ -21,56 +21,97 @@
 namespace cqil {
 
 // ------------------------------------------------------------------------------------------ elementwise
-// nrm[l][m][k] = x[m][k] * rsqrt(mean x[m]^2 + eps) * g[l][k]; one workgroup per token row
+// kVec floats -> one 16-byte vector of the storage type
+__device__ __forceinline__ uint4 pack16(const float (&f)[4], const float*) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+}
+__device__ __forceinline__ uint4 pack16(const float (&f)[8], const bf16_t*) {
+    return make_uint4((uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16),
+                      (uint32_t)f32_to_bf16(f[2]) | ((uint32_t)f32_to_bf16(f[3]) << 16),
+                      (uint32_t)f32_to_bf16(f[4]) | ((uint32_t)f32_to_bf16(f[5]) << 16),
+                      (uint32_t)f32_to_bf16(f[6]) | ((uint32_t)f32_to_bf16(f[7]) << 16));
+}
+
+// nrm[l][m][k] = x[m][k] * rsqrt(mean x[m]^2 + eps) * g[l][k]; one workgroup per token row, 16-byte accesses
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_multi_kernel(const T* __restrict__ x, const T* __restrict__ g,
                                                             T* __restrict__ nrm, int P, int M, int d_model, float eps) {
+    constexpr int V = elem<T>::kVec;
     __shared__ float scratch[16];
     const int m = blockIdx.x, tid = threadIdx.x;
     const T* xr = x + (size_t)m * d_model;
+    const int n_chunks = d_model / V;
     float ss = 0.f;
-    for (int k = tid; k < d_model; k += 256) {
-        const float v = elem<T>::load(xr + k);
-        ss += v * v;
+    for (int c = tid; c < n_chunks; c += 256) {
+        float v[V];
+        elem<T>::unpack(load16(xr + c * V), v);
+#pragma unroll
+        for (int e = 0; e < V; ++e) ss += v[e] * v[e];
     }
     ss = block_sum(ss, scratch);
     const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
-    for (int l = 0; l < P; ++l) {
-        T* out = nrm + ((size_t)l * M + m) * d_model;
-        const T* gl = g + (size_t)l * d_model;
-        for (int k = tid; k < d_model; k += 256) elem<T>::store(out + k, elem<T>::load(xr + k) * r * elem<T>::load(gl + k));
+    for (int c = tid; c < n_chunks; c += 256) {
+        float v[V];
+        elem<T>::unpack(load16(xr + c * V), v);
+        for (int l = 0; l < P; ++l) {
+            float gv[V], o[V];
+            elem<T>::unpack(load16(g + (size_t)l * d_model + c * V), gv);
+#pragma unroll
+            for (int e = 0; e < V; ++e) o[e] = v[e] * r * gv[e];
+            *reinterpret_cast<uint4*>(nrm + ((size_t)l * M + m) * d_model + c * V) = pack16(o, (const T*)nullptr);
+        }
     }
 }
 
-// Rotary embedding and KV append for every (token, layer, head).  grid = (M, P*n_heads), block = head_dim/2.
+// Rotary embedding of q (in place) and k, and the KV append, for one token row per workgroup.  A unit is
+// (layer, head, chunk of kVec rotary pairs): 16-byte accesses on both halves of the head (d_k / 2 % kVec == 0).
 template <typename T>
-__global__ void rope_append_kernel(T* __restrict__ qkv, const float2* __restrict__ rope,
-                                   const int32_t* __restrict__ kv_len, T* __restrict__ kc, T* __restrict__ vc, int P,
-                                   int T_new, int n_heads, int d_k, int max_seq, int b_max) {
+__global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, const float2* __restrict__ rope,
+                                                          const int32_t* __restrict__ kv_len, T* __restrict__ kc,
+                                                          T* __restrict__ vc, int P, int T_new, int n_heads, int d_k,
+                                                          int max_seq, int b_max) {
+    constexpr int V = elem<T>::kVec;
     const int m = blockIdx.x, b = m / T_new, t = m % T_new;
-    const int lh = blockIdx.y, l = lh / n_heads, h = lh % n_heads;
-    const int half = d_k >> 1, i = threadIdx.x;
+    const int half = d_k >> 1, cph = half / V;  // chunks per head half
     const int pos = kv_len[b] + t;
-    if (i >= half || pos < 0 || pos >= max_seq) return;
+    if (pos < 0 || pos >= max_seq) return;
     const size_t d_model = (size_t)n_heads * d_k;
-    T* row = qkv + (size_t)m * P * 3 * d_model + (size_t)l * 3 * d_model + (size_t)h * d_k;
-    const float2 cs = rope[(size_t)pos * half + i];
-    const size_t slot = ((((size_t)l * b_max + b) * n_heads + h) * max_seq + pos) * d_k;
-    {
-        const float a = elem<T>::load(row + i), c = elem<T>::load(row + i + half);
-        elem<T>::store(row + i, a * cs.x - c * cs.y);
-        elem<T>::store(row + i + half, c * cs.x + a * cs.y);
-    }
-    {
+    const int units = P * n_heads * cph;
+    for (int u = threadIdx.x; u < units; u += 256) {
+        const int c = u % cph, lh = u / cph, h = lh % n_heads, l = lh / n_heads;
+        const int i = c * V;
+        T* row = qkv + (size_t)m * P * 3 * d_model + (size_t)l * 3 * d_model + (size_t)h * d_k;
+        const size_t slot = ((((size_t)l * b_max + b) * n_heads + h) * max_seq + pos) * d_k;
+        float cs[2 * V];
+        const float4* rp = reinterpret_cast<const float4*>(rope + (size_t)pos * half + i);
+#pragma unroll
+        for (int e = 0; e < V / 2; ++e) {
+            const float4 r4 = rp[e];
+            cs[4 * e] = r4.x; cs[4 * e + 1] = r4.y; cs[4 * e + 2] = r4.z; cs[4 * e + 3] = r4.w;
+        }
+        float lo[V], hi[V], olo[V], ohi[V];
+        elem<T>::unpack(load16(row + i), lo);
+        elem<T>::unpack(load16(row + i + half), hi);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            olo[e] = lo[e] * cs[2 * e] - hi[e] * cs[2 * e + 1];
+            ohi[e] = hi[e] * cs[2 * e] + lo[e] * cs[2 * e + 1];
+        }
+        *reinterpret_cast<uint4*>(row + i) = pack16(olo, (const T*)nullptr);
+        *reinterpret_cast<uint4*>(row + i + half) = pack16(ohi, (const T*)nullptr);
         const T* kr = row + d_model;
-        const float a = elem<T>::load(kr + i), c = elem<T>::load(kr + i + half);
-        elem<T>::store(kc + slot + i, a * cs.x - c * cs.y);
-        elem<T>::store(kc + slot + i + half, c * cs.x + a * cs.y);
-    }
-    {
+        elem<T>::unpack(load16(kr + i), lo);
+        elem<T>::unpack(load16(kr + i + half), hi);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            olo[e] = lo[e] * cs[2 * e] - hi[e] * cs[2 * e + 1];
+            ohi[e] = hi[e] * cs[2 * e] + lo[e] * cs[2 * e + 1];
+        }
+        *reinterpret_cast<uint4*>(kc + slot + i) = pack16(olo, (const T*)nullptr);
+        *reinterpret_cast<uint4*>(kc + slot + i + half) = pack16(ohi, (const T*)nullptr);
         const T* vr = row + 2 * d_model;
-        vc[slot + i] = vr[i];
-        vc[slot + i + half] = vr[i + half];
+        *reinterpret_cast<uint4*>(vc + slot + i) = load16(vr + i);
+        *reinterpret_cast<uint4*>(vc + slot + i + half) = load16(vr + i + half);
     }
 }
 
@@ -161,36 +202,57 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
 
 // Bypass window, FFN norms and the residual carrier for one token row per workgroup:
 //   h_i = x + sum_{j=max(0,i-d)}^{i} a_j ; nrm_i = RMSNorm(h_i) g_i ; resid = x + sum_j a_j
+// 16-byte accesses: a thread owns chunks of kVec consecutive elements (d_model % kVec == 0).
 template <typename T>
 __global__ __launch_bounds__(256) void bypass_norm_kernel(const T* __restrict__ x, const float* __restrict__ a,
                                                           const T* __restrict__ g_ffn, T* __restrict__ nrm,
                                                           float* __restrict__ resid, int P, int bypass_d, int M,
                                                           int d_model, float eps) {
+    constexpr int V = elem<T>::kVec;
     __shared__ float scratch[16];
     const int m = blockIdx.x, tid = threadIdx.x;
     const T* xr = x + (size_t)m * d_model;
+    const int n_chunks = d_model / V;
+    // h_i for the chunk at k: x plus the window of attention outputs
+    auto window = [&](int k, int jlo, int jhi, float (&hv)[V]) {
+        elem<T>::unpack(load16(xr + k), hv);
+        for (int j = jlo; j <= jhi; ++j) {
+            const float* ap = a + ((size_t)j * M + m) * d_model + k;
+#pragma unroll
+            for (int e = 0; e < V; e += 4) {
+                const float4 t = *reinterpret_cast<const float4*>(ap + e);
+                hv[e] += t.x; hv[e + 1] += t.y; hv[e + 2] += t.z; hv[e + 3] += t.w;
+            }
+        }
+    };
     for (int i = 0; i < P; ++i) {
         const int jlo = max(0, i - bypass_d);
         float ss = 0.f;
-        for (int k = tid; k < d_model; k += 256) {
-            float hv = elem<T>::load(xr + k);
-            for (int j = jlo; j <= i; ++j) hv += a[((size_t)j * M + m) * d_model + k];
-            ss += hv * hv;
+        for (int c = tid; c < n_chunks; c += 256) {
+            float hv[V];
+            window(c * V, jlo, i, hv);
+#pragma unroll
+            for (int e = 0; e < V; ++e) ss += hv[e] * hv[e];
         }
         ss = block_sum(ss, scratch);
         const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
         const T* gi = g_ffn + (size_t)i * d_model;
         T* out = nrm + ((size_t)i * M + m) * d_model;
-        for (int k = tid; k < d_model; k += 256) {
-            float hv = elem<T>::load(xr + k);
-            for (int j = jlo; j <= i; ++j) hv += a[((size_t)j * M + m) * d_model + k];
-            elem<T>::store(out + k, hv * r * elem<T>::load(gi + k));
+        for (int c = tid; c < n_chunks; c += 256) {
+            float hv[V], gv[V];
+            window(c * V, jlo, i, hv);
+            elem<T>::unpack(load16(gi + c * V), gv);
+#pragma unroll
+            for (int e = 0; e < V; ++e) hv[e] = hv[e] * r * gv[e];
+            *reinterpret_cast<uint4*>(out + c * V) = pack16(hv, (const T*)nullptr);
         }
     }
-    for (int k = tid; k < d_model; k += 256) {
-        float v = elem<T>::load(xr + k);
-        for (int j = 0; j < P; ++j) v += a[((size_t)j * M + m) * d_model + k];
-        resid[(size_t)m * d_model + k] = v;
+    for (int c = tid; c < n_chunks; c += 256) {
+        float hv[V];
+        window(c * V, 0, P - 1, hv);
+#pragma unroll
+        for (int e = 0; e < V; e += 4)
+            *reinterpret_cast<float4*>(resid + (size_t)m * d_model + c * V + e) = make_float4(hv[e], hv[e + 1], hv[e + 2], hv[e + 3]);
     }
 }
 
@@ -288,7 +350,7 @@ template <typename T, typename CT, bool ADD_R>
 static hipError_t gemm_any(const T* A, const T* W, CT* C, const float* R, int M, int N, int K, size_t lda, size_t Kp,
                            size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step, size_t sC, hipStream_t st) {
     if constexpr (std::is_same<T, bf16_t>::value) {
-        return gemm_mfma<CT, ADD_R>(g_tune.gemm_tile, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+        return gemm_mfma<CT, ADD_R ? kEpiAddR : kEpiNone>(g_tune.gemm_tile, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
     } else {
         gemm_nt<T, T, CT, ADD_R>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
         return hipSuccess;
@@ -333,7 +395,7 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     hipError_t ge;
     if ((ge = gemm_any<T, T, false>(nrm, wqkv, qkv, nullptr, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm,
                             (size_t)3 * dm, 0, (size_t)3 * dm, st)) != hipSuccess) return ge;
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M, P * nh), dim3(((dk / 2) + 63) / 64 * 64), 0, st,
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M), dim3(256), 0, st,
                        qkv, rope, s.kv_len, (T*)s.kc, (T*)s.vc, P, s.T, nh, dk, d.max_seq, s.b_max);
     const int lps = dk * (int)sizeof(T) / 16;
     bool attn_done = false;
@@ -368,9 +430,13 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     if ((ge = gemm_any<T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, 0, (size_t)dm, Mdm, st)) != hipSuccess) return ge;
     hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(256), 0, st, x, a, g_ffn, nrm, resid, P, bd,
                        M, dm, d.rms_eps);
-    if ((ge = gemm_any<T, T, false>(nrm, wgu, gu, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * 2 * f, P, Mdm, (size_t)2 * f, 0,
-                            (size_t)2 * f, st)) != hipSuccess) return ge;
-    {
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        // gate/up product with SwiGLU in the epilogue: u is written directly, gate and up never reach memory
+        if ((ge = gemm_mfma<bf16_t, kEpiSwiglu>(g_tune.gemm_tile, nrm, wgu, u, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * f,
+                                                 P, Mdm, (size_t)2 * f, 0, (size_t)f, st)) != hipSuccess) return ge;
+    } else {
+        if ((ge = gemm_any<T, T, false>(nrm, wgu, gu, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * 2 * f, P, Mdm, (size_t)2 * f, 0,
+                                (size_t)2 * f, st)) != hipSuccess) return ge;
         const size_t total = (size_t)M * P * f;
         size_t g = (total + 255) / 256;
         if (g > 65536) g = 65536;

@@ -28,6 +28,9 @@ namespace cqil {
 typedef __bf16 gemm_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float gemm_f32x16 __attribute__((ext_vector_type(16)));
 
+// epilogues: plain store, + fp32 residual R[m][n], or SwiGLU over block-interleaved gate / up rows
+constexpr int kEpiNone = 0, kEpiAddR = 1, kEpiSwiglu = 2;
+
 __device__ __forceinline__ void gemm_store4(bf16_t* p, const float (&v)[4]) {
     uint2 o;
     o.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
@@ -39,8 +42,9 @@ __device__ __forceinline__ void gemm_store4(float* p, const float (&v)[4]) {
 }
 
 // N, K: logical sizes of this group's product; N % 4 == 0, K % 8 == 0, M >= 1.  strip_step / ktile_step: group
-// strides in 16-row strips / 32-column tiles inside W.  R (ADD_R): fp32 [M][N] added to the result.
-template <typename CT, bool ADD_R, int WM, int WN>
+// strides in 16-row strips / 32-column tiles inside W.  R (kEpiAddR): fp32 [M][N] added to the result.
+// kEpiSwiglu: N % 32 == 0 rows as blocks of 16 gate + 16 up rows; C gets N / 2 columns per group.
+template <typename CT, int EPI, int WM, int WN>
 __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, CT* __restrict__ C, const float* __restrict__ R, int M,
     int N, int K, size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t strip_step, size_t ktile_step,
@@ -190,24 +194,43 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
         const int m = m0 + 128 * wm + 32 * t + fi;
         if (m >= M) continue;
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
+        for (int s = 0; s < 2; ++s) {
+            if (EPI == kEpiSwiglu) {
+                // rows come as 16 gate rows followed by their 16 up rows: gate row 8 q + 4 h + e (q = 0, 1) and
+                // its up row sit in the same lane, registers 4 q + e and 4 (q + 2) + e.  Output column of the
+                // group: 16 (row block) + 8 q + 4 h + e; N counts gate and up rows, ldc / sC are those of u.
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + 64 * wn + 32 * s + 8 * q + 4 * fgg;
-                if (n >= N) continue;
-                float v[4] = {acc[t][s][4 * q], acc[t][s][4 * q + 1], acc[t][s][4 * q + 2], acc[t][s][4 * q + 3]};
-                if (ADD_R) {
-                    const float4 r = *reinterpret_cast<const float4*>(R + (size_t)m * N + n);
-                    v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w;
+                for (int q = 0; q < 2; ++q) {
+                    const int n = n0 + 64 * wn + 32 * s + 8 * q + 4 * fgg;   // gate row
+                    if (n >= N) continue;
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float gte = acc[t][s][4 * q + e], up = acc[t][s][4 * (q + 2) + e];
+                        v[e] = gte / (1.0f + __expf(-gte)) * up;
+                    }
+                    gemm_store4(C + (size_t)m * ldc + (n0 + 64 * wn + 32 * s) / 2 + 8 * q + 4 * fgg, v);
                 }
-                gemm_store4(C + (size_t)m * ldc + n, v);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + 64 * wn + 32 * s + 8 * q + 4 * fgg;
+                    if (n >= N) continue;
+                    float v[4] = {acc[t][s][4 * q], acc[t][s][4 * q + 1], acc[t][s][4 * q + 2], acc[t][s][4 * q + 3]};
+                    if (EPI == kEpiAddR) {
+                        const float4 r = *reinterpret_cast<const float4*>(R + (size_t)m * N + n);
+                        v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w;
+                    }
+                    gemm_store4(C + (size_t)m * ldc + n, v);
+                }
             }
+        }
     }
 }
 
 // Same argument convention as the plain kernel of the token-parallel path: n_step / k_step are the group strides
 // in weight rows / columns (multiples of 16 / 32).
-template <typename CT, bool ADD_R, int WM, int WN>
+template <typename CT, int EPI, int WM, int WN>
 static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K,
                                    size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step,
                                    size_t k_step, size_t sC, hipStream_t st) {
@@ -218,21 +241,21 @@ static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, cons
     const long supers = (long)groups * ((nx + SN - 1) / SN) * ((ny + SM - 1) / SM);
     const long wgs = (supers + 7) / 8 * 8 * SM * SN;
     if (wgs > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, ADD_R, WM, WN>), dim3((unsigned)wgs), dim3(64 * WM * WN),
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, EPI, WM, WN>), dim3((unsigned)wgs), dim3(64 * WM * WN),
                        lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16, k_step / 32, sC);
     return hipSuccess;
 }
 
 // tile: 1 = 256 tokens x 256 rows (8 waves), 2 = 128 x 256 (4 waves); 0 = default
-template <typename CT, bool ADD_R>
+template <typename CT, int EPI>
 static hipError_t gemm_mfma(int tile_sel, const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K,
                             size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step,
                             size_t sC, hipStream_t st) {
     if (M < 1 || (N & 3) || (K & 7) || K < 8) return hipErrorInvalidValue;
     // default: 128 x 256 (two workgroups per CU overlap each other's barriers and load latency)
     if (tile_sel == 1)
-        return gemm_mfma_launch<CT, ADD_R, 2, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
-    return gemm_mfma_launch<CT, ADD_R, 1, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+        return gemm_mfma_launch<CT, EPI, 2, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+    return gemm_mfma_launch<CT, EPI, 1, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
 }
 
 }  // namespace cqil
