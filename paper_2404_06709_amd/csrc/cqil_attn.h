@@ -8,21 +8,23 @@ namespace cqil {
 // Attention (Eq.2: softmax(QK^T/sqrt(d_k))V) of one query per workgroup over P independent caches.  One workgroup
 // of 16 waves per (layer, token, head): every wave walks the cache in strides, four slot steps (K and V loads of
 // all four in flight) per iteration, with a running maximum / sum / context (online softmax); the 16 partial
-// results are merged through LDS.  q, ctx: fp32 [P][M][d_model].
+// results are merged through LDS.  q: element (l, m, h, i) at q[l * q_ls + m * q_ms + h * d_k + i], type QT (fp32
+// workspace rows of the decode paths, or the storage-type QKV rows of the token-parallel path); ctx: QT
+// [P][M][d_model].  NW waves per workgroup: 16 for few long units, 4 when (layer, token, head) units abound.
 // LPS = lanes that share one cache slot = head_dim * sizeof(T) / 16.
 constexpr int kAttnThreads = 1024;
 constexpr int kAttnWaves = kAttnThreads / kWave;
 
-template <typename T, int LPS>
-__global__ __launch_bounds__(kAttnThreads) void attn_decode_kernel(
-    const float* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc,
-    const int32_t* __restrict__ kv_len, float* __restrict__ ctx, int M, int T_new, int n_heads, int max_seq, int b_max) {
+template <typename T, typename QT, int LPS, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
+    const QT* __restrict__ q, size_t q_ls, size_t q_ms, const T* __restrict__ kc, const T* __restrict__ vc,
+    const int32_t* __restrict__ kv_len, QT* __restrict__ ctx, int M, int T_new, int n_heads, int max_seq, int b_max) {
     constexpr int V = elem<T>::kVec;
     constexpr int DK = LPS * V;
     constexpr int SPW = kWave / LPS;  // slots per wave step
     constexpr int U = 4;              // steps per iteration
-    __shared__ float red_m[kAttnWaves], red_l[kAttnWaves];
-    __shared__ float accs[kAttnWaves][DK];
+    __shared__ float red_m[NW], red_l[NW];
+    __shared__ float accs[NW][DK];
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int sub = lane % LPS, sg = lane / LPS;
@@ -39,9 +41,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_kernel(
     const float scale = 1.0f / sqrtf((float)DK);
     float qv[V];
     {
-        const float* qp = q + ((size_t)l * M + m) * d_model + (size_t)h * DK + sub * V;
+        const QT* qp = q + (size_t)l * q_ls + (size_t)m * q_ms + (size_t)h * DK + sub * V;
 #pragma unroll
-        for (int j = 0; j < V; ++j) qv[j] = qp[j] * scale;
+        for (int j = 0; j < V; ++j) qv[j] = elem<QT>::load(qp + j) * scale;
     }
     const size_t head_off = (((size_t)l * b_max + b) * n_heads + h) * (size_t)max_seq * DK;
     const T* kb = kc + head_off + sub * V;
@@ -51,7 +53,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_kernel(
 #pragma unroll
     for (int j = 0; j < V; ++j) acc[j] = 0.f;
     const int n_steps = (S + SPW - 1) / SPW;
-    for (int i0 = w * U; i0 < n_steps; i0 += kAttnWaves * U) {
+    for (int i0 = w * U; i0 < n_steps; i0 += NW * U) {
         uint4 kraw[U], vraw[U];
         bool ok[U];
 #pragma unroll
@@ -118,15 +120,15 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_kernel(
     if (tid < DK) {
         float gm = red_m[0];
 #pragma unroll
-        for (int i = 1; i < kAttnWaves; ++i) gm = fmaxf(gm, red_m[i]);
+        for (int i = 1; i < NW; ++i) gm = fmaxf(gm, red_m[i]);
         float Ls = 0.f, c = 0.f;
 #pragma unroll
-        for (int i = 0; i < kAttnWaves; ++i) {
+        for (int i = 0; i < NW; ++i) {
             const float e = (red_m[i] == -INFINITY) ? 0.f : expf(red_m[i] - gm);
             Ls += e * red_l[i];
             c += e * accs[i][tid];
         }
-        ctx[((size_t)l * M + m) * d_model + (size_t)h * DK + tid] = c / Ls;
+        elem<QT>::store(ctx + ((size_t)l * M + m) * d_model + (size_t)h * DK + tid, c / Ls);
     }
 }
 

@@ -278,8 +278,9 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     CQIL_MARK(1);
     const int lps = dk * (int)sizeof(T) / 16;
 #define CQIL_ATTN(LPS)                                                                                               \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_decode_kernel<T, LPS>), dim3(P * nh), dim3(kAttnThreads), 0, st, q,      \
-                       (const T*)s.kc, (const T*)s.vc, s.kv_len, ctx, 1, 1, nh, d.max_seq, s.b_max)
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_decode_kernel<T, float, LPS, kAttnWaves>), dim3(P * nh), dim3(kAttnThreads), 0, \
+                       st, (const float*)q, (size_t)dm, (size_t)dm, (const T*)s.kc, (const T*)s.vc, s.kv_len, ctx, 1, 1, nh,    \
+                       d.max_seq, s.b_max)
     switch (lps) {
         case 4: CQIL_ATTN(4); break;
         case 8: CQIL_ATTN(8); break;

@@ -11,6 +11,7 @@
 //   gemm (gate/up)  grouped over layers                                       -> gu  [M][P*2*d_ffn]
 //   swiglu                                                                    -> u   [M][P*d_ffn]
 //   gemm (down)     one contraction over the K-concatenated Wdown + resid     -> x_out
+#include "cqil_attn.h"
 #include "cqil_dev.h"
 #include "cqil_gemv.h"
 #include "cqil_internal.h"
@@ -345,12 +346,15 @@ static void gemm_nt(const AT* A, const BT* B, CT* C, const float* R, int M, int 
                        lda, Kp, ldc, sA, n_step, k_step, sC);
 }
 
-// bf16 products run on the matrix cores, fp32 ones on the plain kernel above
+// bf16 products run on the matrix cores, fp32 ones on the plain kernel above.  part / part_floats: scratch for
+// split-K partial sums of the matrix-core kernel (null: never split).
 template <typename T, typename CT, bool ADD_R>
 static hipError_t gemm_any(const T* A, const T* W, CT* C, const float* R, int M, int N, int K, size_t lda, size_t Kp,
-                           size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step, size_t sC, hipStream_t st) {
+                           size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step, size_t sC, hipStream_t st,
+                           float* part = nullptr, size_t part_floats = 0) {
     if constexpr (std::is_same<T, bf16_t>::value) {
-        return gemm_mfma<CT, ADD_R ? kEpiAddR : kEpiNone>(g_tune.gemm_tile, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+        return gemm_mfma<CT, ADD_R ? kEpiAddR : kEpiNone>(g_tune.gemm_tile, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA,
+                                                          n_step, k_step, sC, st, part, part_floats);
     } else {
         gemm_nt<T, T, CT, ADD_R>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
         return hipSuccess;
@@ -393,15 +397,39 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     hipLaunchKernelGGL(HIP_KERNEL_NAME(rmsnorm_multi_kernel<T>), dim3(M), dim3(256), 0, st, x, g_attn, nrm, P, M, dm,
                        d.rms_eps);
     hipError_t ge;
+    float* part = s.wl.gemm_part_floats ? (float*)(s.ws + s.wl.gemm_part) : nullptr;
     if ((ge = gemm_any<T, T, false>(nrm, wqkv, qkv, nullptr, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm,
-                            (size_t)3 * dm, 0, (size_t)3 * dm, st)) != hipSuccess) return ge;
+                            (size_t)3 * dm, 0, (size_t)3 * dm, st, part, s.wl.gemm_part_floats)) != hipSuccess) return ge;
     hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M), dim3(256), 0, st,
                        qkv, rope, s.kv_len, (T*)s.kc, (T*)s.vc, P, s.T, nh, dk, d.max_seq, s.b_max);
     const int lps = dk * (int)sizeof(T) / 16;
     bool attn_done = false;
+    if (s.T == 1) {
+        // one query per sequence: the streaming kernel of the decode paths, reading q from the QKV rows; four
+        // waves per (layer, sequence, head) once those units outnumber the CUs several times over
+        const bool many = (long)P * M * nh >= 2048;
+#define CQIL_ATTN1(LPS)                                                                                                \
+    if (many)                                                                                                          \
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_decode_kernel<T, T, LPS, 4>), dim3(P * M * nh), dim3(256), 0, st,         \
+                           (const T*)qkv, (size_t)3 * dm, (size_t)P * 3 * dm, (const T*)s.kc, (const T*)s.vc, s.kv_len, ctx, \
+                           M, 1, nh, d.max_seq, s.b_max);                                                              \
+    else                                                                                                               \
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_decode_kernel<T, T, LPS, kAttnWaves>), dim3(P * M * nh),                   \
+                           dim3(kAttnThreads), 0, st, (const T*)qkv, (size_t)3 * dm, (size_t)P * 3 * dm, (const T*)s.kc,    \
+                           (const T*)s.vc, s.kv_len, ctx, M, 1, nh, d.max_seq, s.b_max)
+        switch (lps) {
+            case 4: CQIL_ATTN1(4); break;
+            case 8: CQIL_ATTN1(8); break;
+            case 16: CQIL_ATTN1(16); break;
+            case 32: CQIL_ATTN1(32); break;
+            default: return hipErrorInvalidValue;
+        }
+#undef CQIL_ATTN1
+        attn_done = true;
+    }
     if constexpr (std::is_same<T, bf16_t>::value) {
         // matrix-core attention for the head sizes it is built for; positions were bounded by the caller
-        if (dk == 64 || dk == 128) {
+        if (!attn_done && (dk == 64 || dk == 128)) {
             const dim3 grid((s.T + kPfBQ - 1) / kPfBQ, P * s.B * nh);
             if (dk == 64)
                 hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_prefill_mfma_kernel<64>), grid, dim3(kPfThreads), 0, st,
@@ -427,7 +455,8 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     }
 #undef CQIL_ATTN
     }
-    if ((ge = gemm_any<T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, 0, (size_t)dm, Mdm, st)) != hipSuccess) return ge;
+    if ((ge = gemm_any<T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, 0, (size_t)dm, Mdm, st,
+                                        part, s.wl.gemm_part_floats)) != hipSuccess) return ge;
     hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(256), 0, st, x, a, g_ffn, nrm, resid, P, bd,
                        M, dm, d.rms_eps);
     if constexpr (std::is_same<T, bf16_t>::value) {
@@ -444,7 +473,8 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     }
     {
         const size_t kt = tile<T>::KB, Kp = ((size_t)P * f + kt - 1) / kt * kt;
-        if ((ge = gemm_any<T, T, true>(u, wdown, (T*)s.x_out, resid, M, dm, P * f, (size_t)P * f, Kp, dm, 1, 0, 0, 0, 0, st)) != hipSuccess) return ge;
+        if ((ge = gemm_any<T, T, true>(u, wdown, (T*)s.x_out, resid, M, dm, P * f, (size_t)P * f, Kp, dm, 1, 0, 0, 0, 0, st, part,
+                                       s.wl.gemm_part_floats)) != hipSuccess) return ge;
     }
     if (s.advance) hipLaunchKernelGGL(advance_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st, s.kv_len, s.B, s.T);
     return hipGetLastError();

@@ -85,6 +85,14 @@ int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* W) {
         W->resid = off;   off = align_up(off + M * dm * sizeof(float));
         W->gu = off;      off = align_up(off + M * (size_t)P * 2 * f * es);
         W->u_act = off;   off = align_up(off + M * K * es);
+        if (d->dtype == CQIL_BF16 && M <= 512) {
+            // up to 16 K slices of the widest product (P groups of M x d_model), capped at 128 MiB
+            size_t pf = (size_t)16 * P * M * dm;
+            if (pf > ((size_t)32 << 20)) pf = (size_t)32 << 20;
+            W->gemm_part = off;
+            W->gemm_part_floats = pf;
+            off = align_up(off + pf * sizeof(float));
+        }
     }
     W->total = off;
     return CQIL_OK;

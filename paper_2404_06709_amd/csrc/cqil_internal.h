@@ -40,6 +40,8 @@ struct WsLayout {
     size_t resid;      // f32 [M][d_model]        x + sum_i a_i
     size_t gu;         // act [M][P*2*d_ffn]
     size_t u_act;      // act [M][P*d_ffn]
+    size_t gemm_part;  // f32 split-K partial sums of the matrix-core GEMM (bf16, M <= 512), gemm_part_floats long
+    size_t gemm_part_floats;
     size_t total;
     int n_slices, down_slice;  // K slices of the single-token down projection
     int sk_slices, sk_slice;   // K slices of the small-batch (matrix-core) down projection

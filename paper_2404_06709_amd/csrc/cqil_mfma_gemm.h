@@ -48,7 +48,7 @@ template <typename CT, int EPI, int WM, int WN>
 __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, CT* __restrict__ C, const float* __restrict__ R, int M,
     int N, int K, size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t strip_step, size_t ktile_step,
-    size_t sC) {
+    size_t sC, int ksplit, float* __restrict__ part) {
     constexpr int BM = 128 * WM, BN = 64 * WN, NT = 64 * WM * WN;
     constexpr int TE = 512;            // elements per tile
     constexpr int STAGE = BM * 64;     // activation elements per LDS stage
@@ -65,7 +65,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     const int snx = (nx + SN - 1) / SN, sny = (ny + SM - 1) / SM;
     const int L = blockIdx.x, idx = L >> 3;
     const int S = (idx / ST) * 8 + (L & 7), t = idx % ST;
-    const int z = S / (snx * sny), s2 = S % (snx * sny);
+    const int zk = S / (snx * sny), s2 = S % (snx * sny);
+    const int z = zk / ksplit, ks = zk % ksplit;  // group, K slice (split-K: partial sums go to `part`)
     const int nt = (s2 % snx) * SN + t % SN, mt = (s2 / snx) * SM + t / SN;
     if (z >= groups || nt >= nx || mt >= ny) return;  // padding of the grid (uniform for the workgroup)
     A += (size_t)z * sA;
@@ -153,15 +154,17 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     // that the single barrier of a step is passed while those are in the pipe.  The scheduling barriers keep the
     // compiler from undoing the order.
     uint4 afa[4], afb[4];
-    load_a(0);
+    const int steps_per_slice = (n_steps + ksplit - 1) / ksplit;
+    const int s_beg = ks * steps_per_slice, s_end = min(s_beg + steps_per_slice, n_steps);  // may be empty
+    load_a(s_beg);
 #pragma unroll
-    for (int b = 0; b < 4; ++b) load_w(b, b);
+    for (int b = 0; b < 4; ++b) load_w(b, 4 * s_beg + b);
     store_a(lds);
     __syncthreads();
     read_af(afa, lds, 0);
-    for (int step = 0; step < n_steps; ++step) {
-        bf16_t* cur = lds + (step & 1) * STAGE;
-        bf16_t* nxt = lds + ((step & 1) ^ 1) * STAGE;
+    for (int step = s_beg; step < s_end; ++step) {
+        bf16_t* cur = lds + ((step - s_beg) & 1) * STAGE;
+        bf16_t* nxt = lds + (((step - s_beg) & 1) ^ 1) * STAGE;
         const int k16n = 4 * (step + 1);
         load_a(step + 1);  // beyond the last step: zeros, stored to the idle stage and never used
         read_af(afb, cur, 1);
@@ -189,6 +192,24 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     }
 
     // ---- epilogue: lane (j, h) holds, in registers 4 q .. 4 q + 3, weight rows 8 q + 4 h .. + 3 of token j
+    if (ksplit > 1) {  // partial sums of this K slice: part[ks][z][m][n], fp32; gemm_reduce_kernel finishes
+        float* pz = part + ((size_t)ks * groups + z) * (size_t)M * N;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int m = m0 + 128 * wm + 32 * t + fi;
+            if (m >= M) continue;
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + 64 * wn + 32 * s + 8 * q + 4 * fgg;
+                    if (n >= N) continue;
+                    *reinterpret_cast<float4*>(pz + (size_t)m * N + n) =
+                        make_float4(acc[t][s][4 * q], acc[t][s][4 * q + 1], acc[t][s][4 * q + 2], acc[t][s][4 * q + 3]);
+                }
+        }
+        return;
+    }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int m = m0 + 128 * wm + 32 * t + fi;
@@ -228,21 +249,61 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     }
 }
 
+// C[z][m][n] = sum_ks part[ks][z][m][n] (+ R[m][n]), 4 elements per thread
+template <typename CT, int EPI>
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restrict__ part, CT* __restrict__ C,
+                                                          const float* __restrict__ R, int M, int N, size_t ldc,
+                                                          int groups, size_t sC, int ksplit) {
+    const size_t per_group = (size_t)M * N / 4, total = per_group * groups;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t z = i / per_group, e = (i % per_group) * 4;
+        const size_t m = e / N, n = e % N;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < ksplit; ++ks) {
+            const float4 p4 = *reinterpret_cast<const float4*>(part + (((size_t)ks * groups + z) * M + m) * N + n);
+            v[0] += p4.x; v[1] += p4.y; v[2] += p4.z; v[3] += p4.w;
+        }
+        if (EPI == kEpiAddR) {
+            const float4 r = *reinterpret_cast<const float4*>(R + m * N + n);
+            v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w;
+        }
+        gemm_store4(C + z * sC + m * ldc + n, v);
+    }
+}
+
 // Same argument convention as the plain kernel of the token-parallel path: n_step / k_step are the group strides
-// in weight rows / columns (multiples of 16 / 32).
+// in weight rows / columns (multiples of 16 / 32).  part / part_floats: scratch for split-K partial sums (may be
+// null / 0): when the tile grid is too small to fill the chip, K is cut into slices of whole 64-column steps,
+// each slice writes fp32 partial sums and a second kernel adds them in slice order (deterministic).
 template <typename CT, int EPI, int WM, int WN>
 static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K,
                                    size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step,
-                                   size_t k_step, size_t sC, hipStream_t st) {
+                                   size_t k_step, size_t sC, float* part, size_t part_floats, hipStream_t st) {
     constexpr int BM = 128 * WM, BN = 64 * WN;
     constexpr size_t lds_bytes = 2 * (size_t)BM * 64 * 2;
     constexpr int SN = 8, SM = (WM * WN == 8) ? 4 : 8;
     const int nx = (N + BN - 1) / BN, ny = (M + BM - 1) / BM;
-    const long supers = (long)groups * ((nx + SN - 1) / SN) * ((ny + SM - 1) / SM);
+    int ksplit = 1;
+    if (EPI != kEpiSwiglu && part != nullptr) {
+        const long tiles = (long)nx * ny * groups;
+        const int n_steps = (K + 63) / 64;
+        const size_t per_slice = (size_t)groups * M * N;
+        while (ksplit < 16 && tiles * ksplit < 384 && n_steps / (ksplit * 2) >= 8 &&
+               per_slice * (size_t)(ksplit * 2) <= part_floats)
+            ksplit *= 2;
+    }
+    const long supers = (long)groups * ksplit * ((nx + SN - 1) / SN) * ((ny + SM - 1) / SM);
     const long wgs = (supers + 7) / 8 * 8 * SM * SN;
     if (wgs > 0x7fffffffL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, EPI, WM, WN>), dim3((unsigned)wgs), dim3(64 * WM * WN),
-                       lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16, k_step / 32, sC);
+                       lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16, k_step / 32, sC, ksplit,
+                       part);
+    if (ksplit > 1) {
+        const size_t total = (size_t)groups * M * N / 4;
+        const unsigned g = (unsigned)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_reduce_kernel<CT, EPI>), dim3(g), dim3(256), 0, st, part, C, R, M, N, ldc,
+                           groups, sC, ksplit);
+    }
     return hipSuccess;
 }
 
@@ -250,12 +311,14 @@ static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, cons
 template <typename CT, int EPI>
 static hipError_t gemm_mfma(int tile_sel, const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K,
                             size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step,
-                            size_t sC, hipStream_t st) {
+                            size_t sC, hipStream_t st, float* part = nullptr, size_t part_floats = 0) {
     if (M < 1 || (N & 3) || (K & 7) || K < 8) return hipErrorInvalidValue;
     // default: 128 x 256 (two workgroups per CU overlap each other's barriers and load latency)
     if (tile_sel == 1)
-        return gemm_mfma_launch<CT, EPI, 2, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
-    return gemm_mfma_launch<CT, EPI, 1, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
+        return gemm_mfma_launch<CT, EPI, 2, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, part,
+                                               part_floats, st);
+    return gemm_mfma_launch<CT, EPI, 1, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, part,
+                                           part_floats, st);
 }
 
 }  // namespace cqil

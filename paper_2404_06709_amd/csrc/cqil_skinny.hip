@@ -327,8 +327,9 @@ hipError_t launch_skinny_step(const StepArgs& s, hipStream_t st) {
     {
         const int lps = dk * 2 / 16;
 #define CQIL_ATTN(LPS)                                                                                                \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_decode_kernel<bf16_t, LPS>), dim3(P * M * nh), dim3(kAttnThreads), 0, st, \
-                       q, (const bf16_t*)s.kc, (const bf16_t*)s.vc, s.kv_len, ctx, M, s.T, nh, d.max_seq, s.b_max)
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_decode_kernel<bf16_t, float, LPS, kAttnWaves>), dim3(P * M * nh),         \
+                       dim3(kAttnThreads), 0, st, (const float*)q, (size_t)M * dm, (size_t)dm, (const bf16_t*)s.kc,        \
+                       (const bf16_t*)s.vc, s.kv_len, ctx, M, s.T, nh, d.max_seq, s.b_max)
         switch (lps) {
             case 4: CQIL_ATTN(4); break;
             case 8: CQIL_ATTN(8); break;

@@ -162,6 +162,19 @@ def test_small_batch_matrix_core_path_matches_oracle(shape, P):
     pair.step(pair.hidden(5, 1, seed=6), 1, label="batch 5")
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape,P", [(MID, 2), (synth.Shape(1024, 8, 128, 2816), 3)])
+def test_wide_batch_decode_matches_oracle(shape, P, dtype):
+    """More than 8 sequences, one new token each: token-parallel projections (split along K when the tile grid is
+    small) with the streaming attention kernel reading its queries from the QKV rows."""
+    B = 12
+    pair = Pair(shape, P, dtype, max_seq=300, b_max=B, seed=1200 + P, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([0, 3, 127, 128, 200, 64, 1, 250, 17, 90, 255, 31], seed=8)
+    pair.step(pair.hidden(B, 1, seed=1), 1, label=f"batch {B} {dtype}")
+    pair.step(pair.hidden(B, 1, seed=2), 0, label=f"batch {B} second step {dtype}")
+    pair.step(pair.hidden(9, 1, seed=3), P - 1, label=f"batch 9 {dtype}")
+
+
 def test_prefill_then_decode_equals_one_prefill():
     """Property that holds at any size: prefilling T tokens equals prefilling T-1 and decoding one."""
     pair = Pair(TINY, 2, torch.float32, max_seq=64, b_max=1, seed=11, w_std=0.05, gain_jitter=0.1)
