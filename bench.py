@@ -32,7 +32,7 @@ def kernel_bytes(shape, P, lens, es=2):
     """Algorithmic HBM bytes of each decode kernel for one step of B = len(lens) sequences: every packed weight
     byte once, every valid KV byte once, activations once (lens = cached tokens per sequence before the step)."""
     dm, f, B = shape.d_model, shape.d_ffn, len(lens)
-    ues = 4 if B == 1 else 2   # SwiGLU outputs: fp32 for one token, bf16 for a small batch
+    ues = 4 if B == 1 else 2   # SwiGLU outputs: fp32 for one token, storage type for a batch
     return {
         "qkv_rope": P * 3 * dm * dm * es + B * dm * es + P * dm * es + B * P * dm * 4 + 2 * B * P * dm * es,
         "attn_decode": sum(2 * P * (S + 1) * dm * es for S in lens) + 2 * B * P * dm * 4,
@@ -94,7 +94,7 @@ def main() -> int:
     ap.add_argument("--bypass", type=int, default=1)
     ap.add_argument("--kv-start", type=int, default=512)
     ap.add_argument("--kv-span", type=int, default=128)
-    ap.add_argument("--batch", type=int, default=1, help="sequences per step (bf16 small-batch path for 2..8)")
+    ap.add_argument("--batch", type=int, default=1, help="sequences per step (B > 1: token-parallel kernels; per-kernel figures only for B = 1)")
     ap.add_argument("--kv-hi", type=int, default=0, help="with --batch: lengths uniform in [kv-start, kv-hi]")
     ap.add_argument("--prefill", type=int, default=0, metavar="T",
                     help="time one token-parallel group step over --batch sequences of T new tokens (empty caches) "
@@ -160,23 +160,28 @@ def main() -> int:
     dt = time.perf_counter() - t0
     us_step = dt / args.steps * 1e6
 
-    # per-kernel durations, HIP events on the launch stream, at the mean cache length
+    # per-kernel durations, HIP events on the launch stream, at the mean cache length (single-token path only)
     lens_mean = [S + args.kv_span // 2 for S in lens0]
-    group.set_kv_len(lens_mean)
-    prof_n = 64
-    acc = np.zeros(6)
-    for i in range(prof_n + 8):
-        ms = cq.cqil_decode_step_profile(dims, P, d_byp, group.packed, group.kv, x, y, ws, B)
-        if i >= 8:
-            acc += np.array(ms)
-    k_us = acc / prof_n * 1e3
     kb = kernel_bytes(shape, P, lens_mean)
     names = cq.DECODE_KERNELS
-    per_kernel = {n: {"us": round(float(k_us[i]), 2), "bytes": int(kb[n]),
-                      "gbps": round(kb[n] / (k_us[i] * 1e-6) / 1e9, 1)} for i, n in enumerate(names)}
-    dom = max(names, key=lambda n: kb[n])
-    di = names.index(dom)
-    achieved = kb[dom] / (k_us[di] * 1e-6) / 1e9
+    if B == 1:
+        group.set_kv_len(lens_mean)
+        prof_n = 64
+        acc = np.zeros(6)
+        for i in range(prof_n + 8):
+            ms = cq.cqil_decode_step_profile(dims, P, d_byp, group.packed, group.kv, x, y, ws, B)
+            if i >= 8:
+                acc += np.array(ms)
+        k_us = acc / prof_n * 1e3
+        per_kernel = {n: {"us": round(float(k_us[i]), 2), "bytes": int(kb[n]),
+                          "gbps": round(kb[n] / (k_us[i] * 1e-6) / 1e9, 1)} for i, n in enumerate(names)}
+        dom = max(names, key=lambda n: kb[n])
+        achieved = kb[dom] / (k_us[names.index(dom)] * 1e-6) / 1e9
+    else:
+        # a batch runs the token-parallel kernels: the roofline figure is that of the whole step
+        per_kernel = None
+        dom = "whole group step"
+        achieved = sum(kb.values()) / (us_step * 1e-6) / 1e9
     step_bytes = sum(kb.values())
 
     out = {

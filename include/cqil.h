@@ -131,7 +131,7 @@ int cqil_group_forward(const cqil_dims *dims, int P, int bypass_d, const void *p
                        const void *x_in, void *x_out, int B, int T, int advance_kv_len, void *workspace,
                        size_t workspace_bytes, void *stream);
 
-/* Measurement aid for a decode step (T == 1, kv_len not advanced; B == 1, or bf16 with 2 <= B <= 8): the same six
+/* Measurement aid for a single-token decode step (B must be 1, T == 1, kv_len not advanced): the same six
  * kernels as cqil_group_forward, with HIP events recorded on `stream` around each of them.  Waits for the
  * step to finish and writes the six elapsed times in milliseconds to kernel_ms_out (host, 6 floats), in
  * the order: QKV projection (+norm, rotary, append), attention, O projection, gate/up (+bypass, norm,

@@ -191,7 +191,7 @@ DECODE_KERNELS = ("qkv_rope", "attn_decode", "oproj", "gateup", "down", "merge")
 def cqil_decode_step_profile(dims: cqil_dims, P: int, bypass_d: int, packed: torch.Tensor, kv: cqil_kv,
                              x_in: torch.Tensor, x_out: torch.Tensor, workspace: torch.Tensor,
                              B: int = 1) -> List[float]:
-    """Per-kernel milliseconds of one decode step (one new token for each of B sequences), in DECODE_KERNELS order."""
+    """Per-kernel milliseconds of one single-token decode step (B must be 1), in DECODE_KERNELS order."""
     ms = (C.c_float * 6)()
     rc = lib().cqil_decode_step_profile(C.byref(dims), P, bypass_d, _ptr(packed), C.byref(kv), _ptr(x_in), _ptr(x_out),
                                         B, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(), ms)

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcqil.so")
-SOURCES = ["cqil_host.hip", "cqil_pack.hip", "cqil_decode.hip", "cqil_generic.hip", "cqil_skinny.hip"]
+SOURCES = ["cqil_host.hip", "cqil_pack.hip", "cqil_decode.hip", "cqil_generic.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",

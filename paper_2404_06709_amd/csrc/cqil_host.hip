@@ -65,20 +65,10 @@ int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* W) {
     W->q = off;         off = align_up(off + (size_t)P * M * dm * sizeof(float));
     W->ctx = off;       off = align_up(off + (size_t)P * M * dm * sizeof(float));
     W->a = off;         off = align_up(off + (size_t)P * M * dm * sizeof(float));
-    // small-batch path: slices of at most 4096 columns, equal lengths, multiples of 256 (8 tiles)
-    int sks = (int)((Kp + 4095) / 4096);
-    size_t skl = ((Kp + sks - 1) / sks + 255) / 256 * 256;
-    sks = (int)((Kp + skl - 1) / skl);
-    W->sk_slices = sks;
-    W->sk_slice = (int)skl;
     if (M == 1) {
         W->u = off;         off = align_up(off + K * sizeof(float));
         W->down_part = off; off = align_up(off + (size_t)ns * dm * sizeof(float));
     } else {
-        if (skinny_supported(*d, P, (int)M)) {
-            W->u = off;         off = align_up(off + M * K * sizeof(uint16_t));
-            W->down_part = off; off = align_up(off + (size_t)sks * M * dm * sizeof(float));
-        }
         W->nrm = off;     off = align_up(off + (size_t)P * M * dm * es);
         W->qkv = off;     off = align_up(off + M * (size_t)P * 3 * dm * es);
         W->ctx_act = off; off = align_up(off + (size_t)P * M * dm * es);
@@ -223,8 +213,7 @@ static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const 
     a.packed = (const char*)packed;
     a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.b_max = b_max; a.max_kv_len = max_kv_len;
     a.x_in = x_in; a.x_out = x_out; a.ws = (char*)workspace;
-    hipError_t e = (B * T == 1) ? launch_decode_step(a, st)
-                   : skinny_supported(*dims, P, B * T) ? launch_skinny_step(a, st) : launch_generic_step(a, st);
+    hipError_t e = (B * T == 1) ? launch_decode_step(a, st) : launch_generic_step(a, st);
     return e == hipSuccess ? CQIL_OK : CQIL_EHIP;
 }
 
@@ -242,8 +231,8 @@ int cqil_decode_step_profile(const cqil_dims* dims, int P, int bypass_d, const v
                              const void* x_in, void* x_out, int B, void* workspace, size_t workspace_bytes,
                              void* stream, float* kernel_ms_out) {
     if (!kv || !kernel_ms_out) return CQIL_EINVAL;
-    // only the paths that run the six decode kernels record events
-    if (B < 1 || !dims || !(B == 1 || skinny_supported(*dims, P, B))) return CQIL_EINVAL;
+    // only the single-token path (the six decode kernels) records events
+    if (B != 1 || !dims) return CQIL_EINVAL;
     hipEvent_t ev[7];
     for (int i = 0; i < 7; ++i)
         if (hipEventCreate(&ev[i]) != hipSuccess) return CQIL_EHIP;

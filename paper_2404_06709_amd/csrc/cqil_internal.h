@@ -31,8 +31,8 @@ struct WsLayout {
     size_t q;          // f32 [P][M][d_model]     rotated queries
     size_t ctx;        // f32 [P][M][d_model]     attention context (heads concatenated)
     size_t a;          // f32 [P][M][d_model]     attention outputs a_i
-    size_t u;          // f32 [P*d_ffn] (single token) or bf16 [M][P*d_ffn] (small batch): SwiGLU outputs
-    size_t down_part;  // f32 [slices][M][d_model] split-K partials of the down projection
+    size_t u;          // f32 [P*d_ffn] (single token): SwiGLU outputs
+    size_t down_part;  // f32 [slices][d_model] split-K partials of the single-token down projection
     // token-parallel path (M = B*T > 1); act = dtype of the call
     size_t nrm;        // act [P][M][d_model]     normalised inputs (attention norm, later FFN norm)
     size_t qkv;        // act [M][P*3*d_model]
@@ -44,7 +44,6 @@ struct WsLayout {
     size_t gemm_part_floats;
     size_t total;
     int n_slices, down_slice;  // K slices of the single-token down projection
-    int sk_slices, sk_slice;   // K slices of the small-batch (matrix-core) down projection
 };
 
 int check_dims(const cqil_dims* d, int P);
@@ -75,8 +74,6 @@ struct StepArgs {
 
 hipError_t launch_decode_step(const StepArgs& a, hipStream_t st);   // B*T == 1
 hipError_t launch_generic_step(const StepArgs& a, hipStream_t st);  // any B, T
-bool skinny_supported(const cqil_dims& d, int P, int M);
-hipError_t launch_skinny_step(const StepArgs& a, hipStream_t st);   // bf16, 2 <= B*T <= 8
 
 struct HeadArgs {
     cqil_dims d;

@@ -150,8 +150,8 @@ def test_token_parallel_path_matches_oracle(shape, dtype):
 
 
 @pytest.mark.parametrize("shape,P", [(MID, 1), (MID, 4), (synth.Shape(256, 4, 64, 2752), 2), (synth.Shape(1024, 8, 128, 2816), 3)])
-def test_small_batch_matrix_core_path_matches_oracle(shape, P):
-    """bf16, 2..8 token rows per call: the decode kernels that feed the matrix cores."""
+def test_small_batch_decode_matches_oracle(shape, P):
+    """bf16, 2..8 token rows per call (token-parallel kernels with few rows; K-split projections)."""
     pair = Pair(shape, P, torch.bfloat16, max_seq=300, b_max=8, seed=900 + P, w_std=0.05, gain_jitter=0.1)
     pair.fill_cache([0, 3, 127, 128, 200, 64, 1, 250], seed=6)
     pair.step(pair.hidden(8, 1, seed=1), 1, label="batch 8")
