@@ -182,7 +182,8 @@ def seq_layer(dims: Dims, layer: dict, kcache, vcache, kv_len, x) -> np.ndarray:
 
 
 def group_forward(dims: Dims, layers: Sequence[dict], d: int, kcache, vcache, kv_len, x, debug: bool = False):
-    """Eq.3 / Eq.4.  Returns x_out, or (x_out, attn[P,B,T,dm], h[P,B,T,dm]) with debug=True."""
+    """Eq.3 / Eq.4 (d >= 0) or the attention-FFN parallel form of App. A, Eq.5 (d = -1).  Returns x_out, or
+    (x_out, attn[P,B,T,dm], h[P,B,T,dm]) with debug=True."""
     x = _f64(x)
     B, T, dm = x.shape
     P = len(layers)

@@ -218,13 +218,16 @@ int orc_seq_layer(const orc_dims *D, const orc_layer *L, double *kcache, double 
  *   attn_i = ATTN_{l_i}(x)                                      i = 0..P-1, each with its own cache
  *   h_i    = x + attn_i + sum_{j : 1 <= i-j <= d} attn_j         FFN input of layer i (bypass)
  *   x_out  = x + sum_i attn_i + sum_i FFN_{l_i}(h_i)
+ * d = -1 selects the attention-FFN parallel form of App. A (Eq.5), applied to every layer of the group:
+ *   h_i    = x                                                   (the feed-forward module reads the shared input)
+ *   x_out  = x + sum_i attn_i + sum_i FFN_{l_i}(x)
  * dbg_attn, dbg_h: optional [P][B][T][d_model] copies of attn_i and h_i (may be NULL).
  * kv_len is not advanced here.
  */
 int orc_group_forward(const orc_dims *D, int P, int d, const orc_layer *layers, double *kcache,
                       double *vcache, int b_max, const int32_t *kv_len, const double *x, double *x_out,
                       int B, int T, double *dbg_attn, double *dbg_h) {
-    if (P < 1 || d < 0) return -1;
+    if (P < 1 || d < -1) return -1;
     size_t n = (size_t)B * (size_t)T * (size_t)D->d_model;
     double *attn = malloc(sizeof(double) * n * (size_t)P);
     double *h = malloc(sizeof(double) * n);
@@ -239,7 +242,11 @@ int orc_group_forward(const orc_dims *D, int P, int d, const orc_layer *layers, 
     for (int i = 0; i < P; ++i)
         for (size_t e = 0; e < n; ++e) acc[e] += attn[n * (size_t)i + e];
     for (int i = 0; i < P; ++i) {
-        for (size_t e = 0; e < n; ++e) h[e] = x[e] + attn[n * (size_t)i + e];
+        if (d == -1) {
+            memcpy(h, x, sizeof(double) * n);                              /* Eq.5 */
+        } else {
+            for (size_t e = 0; e < n; ++e) h[e] = x[e] + attn[n * (size_t)i + e];
+        }
         for (int j = 0; j < P; ++j) {
             int dist = i - j;
             if (dist >= 1 && dist <= d)

@@ -197,6 +197,60 @@ def test_group_forward_matches_eq4_written_with_library_modules(P, d):
     np.testing.assert_allclose(out[0], ref.numpy(), rtol=1e-10, atol=1e-12)
 
 
+# ----------------------------------------------------------------------------- App. A, Eq.5 (d = -1)
+@pytest.mark.parametrize("P", [1, 3])
+def test_attention_ffn_parallel_form_matches_library_modules(P):
+    """x_out = x + sum ATTN_l(x) + sum FFN_l(x): the feed-forward modules read the shared input, not x + a."""
+    D = tiny_dims()
+    tl, nl = tiny_layers(P)
+    S, T = 4, 3
+    gen = synth.generator(34)
+    kc, vc = orc.new_cache(P, 1, D), orc.new_cache(P, 1, D)
+    kp = [synth.normal((D.n_heads, S, D.head_dim), 1.0, torch.float32, gen).double() for _ in range(P)]
+    vp = [synth.normal((D.n_heads, S, D.head_dim), 1.0, torch.float32, gen).double() for _ in range(P)]
+    for i in range(P):
+        kc[i, 0, :, :S] = kp[i].numpy(); vc[i, 0, :, :S] = vp[i].numpy()
+    x = hidden(1, T)
+    out, attn_dbg, h_dbg = orc.group_forward(D, nl, -1, kc, vc, [S], x, debug=True)
+    xt = torch.from_numpy(x[0])
+    ref = xt.clone()
+    for l in range(P):
+        ref = ref + torch_attn(tl[l], xt, kp[l], vp[l])[0] + torch_ffn(tl[l], xt)
+    np.testing.assert_allclose(out[0], ref.numpy(), rtol=1e-10, atol=1e-12)
+    for l in range(P):
+        np.testing.assert_array_equal(h_dbg[l], x)          # FFN input is x itself
+    # it differs from Eq.3 (d = 0) whenever the attention output is not zero
+    kc2, vc2 = kc.copy(), vc.copy()
+    eq3 = orc.group_forward(D, nl, 0, kc2, vc2, [S], x)
+    assert np.abs(eq3 - out).max() > 1e-6
+
+
+def test_attention_ffn_parallel_form_equals_eq1_when_attention_is_silent():
+    """With W^O = 0 the attention output vanishes and Eq.5 and Eq.1 coincide bit for bit."""
+    D = tiny_dims()
+    _, nl = tiny_layers(1)
+    nl[0] = dict(nl[0]); nl[0]["wo"] = np.zeros_like(nl[0]["wo"])
+    S = [5]
+    x = hidden(1, 2)
+    kc, vc = _filled_caches(1, 1, D, S)
+    a = orc.group_forward(D, nl, -1, kc.copy(), vc.copy(), S, x)
+    b = orc.seq_layer(D, nl[0], kc.copy(), vc.copy(), S, x)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_attention_ffn_parallel_form_is_additive_in_the_attention_branch():
+    """x_out(W^O) - x_out(0) = ATTN(x): the feed-forward term does not see the attention output."""
+    D = tiny_dims()
+    _, nl = tiny_layers(2)
+    S = [6]
+    x = hidden(1, 3)
+    kc, vc = _filled_caches(2, 1, D, S)
+    full, attn, _ = orc.group_forward(D, nl, -1, kc.copy(), vc.copy(), S, x, debug=True)
+    silent = [dict(l, wo=np.zeros_like(l["wo"])) for l in nl]
+    base = orc.group_forward(D, silent, -1, kc.copy(), vc.copy(), S, x)
+    np.testing.assert_allclose(full - base, attn.sum(axis=0), rtol=0, atol=1e-12)
+
+
 # ----------------------------------------------------------------------------- invariants I1-I7
 def _filled_caches(P, B, D, S, seed=55):
     gen = synth.generator(seed)
