@@ -45,6 +45,9 @@ typedef enum {
 
 typedef enum { CQIL_F32 = 0, CQIL_BF16 = 1 } cqil_dtype;
 
+/* Value of bypass_d that selects the attention-FFN parallel form (App. A, Eq.5) instead of Eq.4. */
+#define CQIL_ATTN_FFN_PARALLEL (-1)
+
 /* Shape of one decoder layer.  Requirements: n_heads * head_dim == d_model; head_dim a power of two,
  * 32..256 (bf16) or 32..128 (fp32); d_model % 32 == 0, at most 14336; d_ffn % 16 == 0; max_seq >= 1. */
 typedef struct {
@@ -124,7 +127,9 @@ int cqil_pack_group(const cqil_dims *dims, int P, const cqil_layer *layers /* ho
  *   x_out  = x + sum_i attn_i + sum_i FFN_i(h_i)
  * x_in, x_out: [B][T][d_model] dtype; x_out may alias x_in.  T == 1 is a decode step, T > 1 a
  * prefill chunk at positions kv_len[b] .. kv_len[b]+T-1 (causal over cache + new tokens).
- * bypass_d < 0 is CQIL_EINVAL; bypass_d >= P acts as P-1.  advance_kv_len != 0 adds T to
+ * bypass_d >= P acts as P-1; bypass_d == CQIL_ATTN_FFN_PARALLEL (-1) selects the attention-FFN parallel form
+ * of App. A (Eq.5) for every layer of the group: each feed-forward module reads x itself,
+ * x_out = x + sum_l ATTN_l(x) + sum_l FFN_l(x); any other negative value is CQIL_EINVAL.  advance_kv_len != 0 adds T to
  * kv_len[b] (b < B) and to kv->max_kv_len after the step. workspace: cqil_workspace_bytes()
  * bytes, 256-byte aligned, contents undefined on entry and exit. */
 int cqil_group_forward(const cqil_dims *dims, int P, int bypass_d, const void *packed, cqil_kv *kv /* host */,

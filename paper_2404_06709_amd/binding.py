@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcqil.so")
 
 CQIL_F32, CQIL_BF16 = 0, 1
+CQIL_ATTN_FFN_PARALLEL = -1   # bypass_d value selecting App. A, Eq.5
 CQIL_OK, CQIL_EINVAL, CQIL_ESIZE, CQIL_ERANGE, CQIL_EHIP = 0, -1, -2, -3, -4
 
 

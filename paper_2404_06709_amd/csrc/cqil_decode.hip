@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
     float* scratch = red + kRedFloats;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int l = blockIdx.y;
-    const int jlo = max(0, l - bypass_d);
+    const int jlo = bypass_d < 0 ? l + 1 : max(0, l - bypass_d);  // negative: Eq.5, the input is x alone
     float ss = 0.f;
     for (int k = tid; k < d_model; k += kThreads) {
         float hv = elem<T>::load(x + k);

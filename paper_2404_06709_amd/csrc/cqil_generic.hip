@@ -227,7 +227,7 @@ __global__ __launch_bounds__(256) void bypass_norm_kernel(const T* __restrict__ 
         }
     };
     for (int i = 0; i < P; ++i) {
-        const int jlo = max(0, i - bypass_d);
+        const int jlo = bypass_d < 0 ? i + 1 : max(0, i - bypass_d);  // negative: Eq.5, the input is x alone
         float ss = 0.f;
         for (int c = tid; c < n_chunks; c += 256) {
             float hv[V];

@@ -198,7 +198,7 @@ static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const 
     a.ev = ev;
     int rc = packed_layout(dims, P, &a.pl);
     if (rc) return rc;
-    if (bypass_d < 0 || B < 1 || T < 1) return CQIL_EINVAL;
+    if (bypass_d < CQIL_ATTN_FFN_PARALLEL || B < 1 || T < 1) return CQIL_EINVAL;
     if (!packed || !kc || !vc || !kv_len || !x_in || !x_out || !workspace) return CQIL_EINVAL;
     if (!aligned16(packed) || !aligned16(kc) || !aligned16(vc) || !aligned16(x_in) || !aligned16(x_out) ||
         !aligned16(workspace))
@@ -281,7 +281,7 @@ int cqil_model_forward(cqil_model* m, const int32_t* tokens, int B, int T, int b
     if (!tokens || !workspace || !m->packed || !m->k_cache || !m->v_cache || !m->kv_len || !m->embedding ||
         !m->g_final || !m->lm_head)
         return CQIL_EINVAL;
-    if (bypass_d < 0) return CQIL_EINVAL;
+    if (bypass_d < CQIL_ATTN_FFN_PARALLEL) return CQIL_EINVAL;
     if (!aligned16(workspace) || !aligned16(m->embedding) || !aligned16(m->lm_head) || !aligned16(m->g_final))
         return CQIL_EINVAL;
     if (hidden_out && !aligned16(hidden_out)) return CQIL_EINVAL;

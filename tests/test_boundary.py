@@ -88,7 +88,7 @@ def _call_group(d, P=2, bypass=1, packed=0x1000, k=0x1000, v=0x1000, kvl=0x1000,
 def test_group_forward_validates_before_launching():
     """Every call below must fail on the host: the fake pointers are never dereferenced."""
     d = dims(max_seq=64)
-    assert _call_group(d, bypass=-1) == cq.CQIL_EINVAL
+    assert _call_group(d, bypass=-2) == cq.CQIL_EINVAL          # -1 is the attention-FFN parallel form
     assert _call_group(d, P=0) == cq.CQIL_EINVAL
     assert _call_group(d, packed=None) == cq.CQIL_EINVAL
     assert _call_group(d, x=None) == cq.CQIL_EINVAL
@@ -149,6 +149,6 @@ def test_model_forward_validates_before_launching():
     m.max_kv_len = 62
     assert lib.cqil_model_forward(C.byref(m), 0x1000, 1, 4, 1, 0, None, None, None, 0x1000, need, None) == cq.CQIL_ERANGE
     m.max_kv_len = 0
-    assert lib.cqil_model_forward(C.byref(m), 0x1000, 1, 4, -1, 0, None, None, None, 0x1000, need, None) == cq.CQIL_EINVAL
+    assert lib.cqil_model_forward(C.byref(m), 0x1000, 1, 4, -2, 0, None, None, None, 0x1000, need, None) == cq.CQIL_EINVAL
     gs[1] = 0
     assert lib.cqil_model_workspace_bytes(C.byref(m), 1, 4) == 0

@@ -175,6 +175,28 @@ def test_wide_batch_decode_matches_oracle(shape, P, dtype):
     pair.step(pair.hidden(9, 1, seed=3), P - 1, label=f"batch 9 {dtype}")
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape,P", [(TINY, 1), (MID, 3)])
+def test_attention_ffn_parallel_form_matches_oracle(shape, P, dtype):
+    """App. A, Eq.5 (bypass_d = -1): every feed-forward module reads the shared input itself.  Decode steps,
+    a prefill chunk and a batch of decode rows; and the result must be told apart from Eq.3's."""
+    d = cq.CQIL_ATTN_FFN_PARALLEL
+    pair = Pair(shape, P, dtype, max_seq=200, b_max=10, seed=500 + P, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([9, 0, 130, 4, 77, 1, 33, 64, 12, 100], seed=9)
+    pair.step(pair.hidden(1, 1, seed=1), d, label=f"Eq.5 decode {dtype}")
+    pair.step(pair.hidden(3, 5, seed=2), d, label=f"Eq.5 prefill {dtype}")
+    pair.step(pair.hidden(10, 1, seed=3), d, label=f"Eq.5 batch of rows {dtype}")
+    # discrimination: on the same state, Eq.3 (d = 0) gives a visibly different answer
+    x = pair.hidden(1, 1, seed=4)
+    lens = pair.lens[:1].copy()
+    okc, ovc = pair.okc.copy(), pair.ovc.copy()
+    eq5 = orc.group_forward(pair.od, pair.np_layers, d, okc, ovc, lens, synth.widen(x))
+    eq3 = orc.group_forward(pair.od, pair.np_layers, 0, pair.okc.copy(), pair.ovc.copy(), lens, synth.widen(x))
+    y, _ = pair.step(x, d, label=f"Eq.5 decode again {dtype}")
+    assert rel_err(eq3, eq5) > 4 * TOL[dtype], "the test inputs do not separate Eq.5 from Eq.3"
+    assert rel_err(synth.widen(y), eq5) <= TOL[dtype] < rel_err(synth.widen(y), eq3)
+
+
 def test_prefill_then_decode_equals_one_prefill():
     """Property that holds at any size: prefilling T tokens equals prefilling T-1 and decoding one."""
     pair = Pair(TINY, 2, torch.float32, max_seq=64, b_max=1, seed=11, w_std=0.05, gain_jitter=0.1)
