@@ -123,6 +123,24 @@ def test_decode_step_matches_oracle(shape, dtype):
                 pair.step(pair.hidden(1, 1, seed=7 + i), d, label=f"decode {dtype} P={P} S={S}")
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("P", [3, 8])
+def test_every_bypass_distance_decode_and_prefill(P, dtype):
+    """Sec.4.3 / Eq.4 for d = 0 .. P-1 (and one value beyond, which acts as P-1), group sizes 3 and 8, on both
+    the single-token kernels and the token-parallel ones."""
+    pair = Pair(TINY, P, dtype, max_seq=160, b_max=2, seed=2000 + P, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([40, 3], seed=12)
+    for d in list(range(P)) + [P + 2]:
+        pair.step(pair.hidden(1, 1, seed=10 + d), d, label=f"P={P} d={d} decode {dtype}")
+        pair.step(pair.hidden(2, 3, seed=30 + d), d, label=f"P={P} d={d} prefill {dtype}")
+    # a distance beyond the group equals the largest one: same state, same input
+    x = pair.hidden(1, 1, seed=99).cuda()
+    lens = pair.lens[:1].tolist()
+    pair.group.set_kv_len(lens); a = pair.group.forward(x, P - 1, advance=False).clone()
+    pair.group.set_kv_len(lens); b = pair.group.forward(x, P + 5, advance=False).clone()
+    assert torch.equal(a, b)
+
+
 def test_decode_is_deterministic_and_in_place():
     pair = Pair(TINY, 4, torch.float32, max_seq=300, b_max=1, seed=5, w_std=0.05, gain_jitter=0.1)
     pair.fill_cache([260], seed=9)
@@ -289,6 +307,34 @@ def test_model_forward_teacher_forced(dtype):
         assert kv_len.cpu()[0].item() == olen and model.c.max_kv_len == olen
         tokens = torch.from_numpy(ref["next"].reshape(1, 1).astype(np.int32))
     say(f"  greedy tokens agreeing with the oracle: {agree}/9")
+
+
+@pytest.mark.parametrize("L,p,s,e", [(7, 3, 2, 6), (9, 4, 1, 9), (5, 8, 2, 4)])
+def test_model_forward_general_partitions(L, p, s, e):
+    """Sec.4.2 partitions with a ragged trailing group, a group at the very bottom and top, and p larger than
+    the grouped range: prefill and two decode steps against the oracle, fp32."""
+    dtype, vocab, max_seq = torch.float32, 211, 24
+    sizes = cq.cqil_partition(L, p, s, e)
+    assert sizes == orc.partition(L, p, s, e) and sum(sizes) == L
+    model, groups, kv_len, nl, emb, gfin, head = _tiny_model(dtype, sizes, vocab, max_seq, seed=4000 + L)
+    od = odims(TINY, max_seq, dtype)
+    okc, ovc = orc.new_cache(L, 1, od), orc.new_cache(L, 1, od)
+    tokens = torch.randint(0, vocab, (1, 7), generator=synth.generator(3)).to(torch.int32)
+    olen = 0
+    for step in range(3):
+        T = tokens.shape[1]
+        ws = torch.empty(cq.cqil_model_workspace_bytes(model, 1, T), dtype=torch.uint8, device="cuda")
+        logits = torch.empty(1, vocab, dtype=torch.float32, device="cuda")
+        hid = torch.empty(1, T, TINY.d_model, dtype=dtype, device="cuda")
+        cq.cqil_model_forward(model, tokens.cuda(), 1, T, 2, True, hid, logits, None, ws)
+        torch.cuda.synchronize()
+        ref = orc.model_forward(od, nl, sizes, 2, emb, gfin, head, okc, ovc, [olen], tokens.numpy())
+        olen += T
+        e_h = rel_err(synth.widen(hid.cpu()), ref["hidden"])
+        e_l = rel_err(logits.cpu().numpy(), ref["logits"])
+        say(f"  partition {sizes} step {step}: hidden {e_h:.2e} logits {e_l:.2e}")
+        assert e_h <= 4 * TOL[dtype] and e_l <= 4 * TOL[dtype]
+        tokens = torch.from_numpy(ref["next"].reshape(1, 1).astype(np.int32))
 
 
 def test_model_forward_equals_chain_of_group_calls():
