@@ -121,6 +121,15 @@ int cqil_partition(int L, int p, int s, int e, int *group_sizes_out, int *n_grou
 int cqil_pack_group(const cqil_dims *dims, int P, const cqil_layer *layers /* host */, void *packed,
                     size_t packed_bytes, void *stream);
 
+/* Folds a LoRA adapter into a source weight matrix before packing (Sec.5.1, App. C: the paper fine-tunes
+ * adapters on every linear matrix of the attention and feed-forward modules with alpha = rank, i.e. scale 1):
+ *   W[o][k] += scale * sum_j Bm[o][j] * A[j][k]
+ * W [n_out][n_in] (device, row-major, updated in place), A [rank][n_in], Bm [n_out][rank], all of `dtype`
+ * (cqil_dtype); fp32 accumulation and one rounding to dtype.  n_in must be a multiple of 16 / sizeof(dtype),
+ * 1 <= rank <= 1024, W and A 16-byte aligned; otherwise CQIL_EINVAL.  Asynchronous on `stream`. */
+int cqil_merge_lora(void *W, const void *A, const void *Bm, int dtype, int n_out, int n_in, int rank, float scale,
+                    void *stream);
+
 /* One group step (Eq.4; Eq.3 when bypass_d == 0; Eq.1 when P == 1):
  *   attn_i = ATTN_i(x)                                   i = 0..P-1, all from the same x
  *   h_i    = x + attn_i + sum_{j : 1 <= i-j <= d} attn_j

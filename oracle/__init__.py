@@ -120,6 +120,18 @@ def linear(W: np.ndarray, x) -> np.ndarray:
     return y
 
 
+def merge_lora(W: np.ndarray, A: np.ndarray, Bm: np.ndarray, scale: float = 1.0) -> np.ndarray:
+    """W + scale * Bm @ A in float64 (unrounded): W [out,in], A [r,in], Bm [out,r], one storage type."""
+    W, A, Bm = np.ascontiguousarray(W), np.ascontiguousarray(A), np.ascontiguousarray(Bm)
+    assert _wdtype(W) == _wdtype(A) == _wdtype(Bm)
+    n_out, n_in = W.shape
+    r = A.shape[0]
+    assert A.shape == (r, n_in) and Bm.shape == (n_out, r)
+    out = np.empty((n_out, n_in), dtype=np.float64)
+    lib().orc_merge_lora(_p(W), _p(A), _p(Bm), _wdtype(W), n_out, n_in, r, C.c_double(scale), _p(out))
+    return out
+
+
 def rmsnorm(x, g: np.ndarray, eps: float) -> np.ndarray:
     x = _f64(x)
     g = np.ascontiguousarray(g)

@@ -15,6 +15,7 @@
  *   orc_attn_module   Eq.2: ATTN(x) = MHA(Norm(x)), heads, softmax(QK^T/sqrt(d_k))V, Concat(...)W^O
  *   orc_ffn_module    Eq.2: FFN(x) = W_2 f(W_1 Norm(x)), instantiated as LLaMA's bias-free SwiGLU
  *   orc_seq_layer     Eq.1: x_{l+1} = x_l + ATTN_l(x_l) + FFN_l(x_l + ATTN_l(x_l))
+ *   orc_merge_lora    W + BA, the merged form of the LoRA adapters the paper fine-tunes (Sec.5.1, App. C)
  *   orc_group_forward Eq.3 (d = 0) and Eq.4 (bypass distance d), Alg.1's middle loop
  *   orc_partition     Sec.4.2 "Layer Partition and Parallelism": (p, s, e) -> group sizes
  *   orc_model_forward Alg.1 as a whole, with the LLaMA embedding / final norm / lm head around it
@@ -83,6 +84,21 @@ void orc_linear(const void *W, int dtype, int n_out, int n_in, const double *x, 
         for (int k = 0; k < n_in; ++k) acc += wload(W, dtype, base + (size_t)k) * x[k];
         y[o] = acc;
     }
+}
+
+/* LoRA merge (Sec.5.1 / App. C: adapters on every linear matrix, alpha = rank, i.e. scale 1):
+ *   out[o,k] = W[o,k] + scale * sum_j Bm[o,j] A[j,k]      W [n_out,n_in], A [r,n_in], Bm [n_out,r]
+ * The sum is returned unrounded; the caller rounds it to the storage type. */
+void orc_merge_lora(const void *W, const void *A, const void *Bm, int dtype, int n_out, int n_in, int r,
+                    double scale, double *out) {
+#pragma omp parallel for schedule(static)
+    for (int o = 0; o < n_out; ++o)
+        for (int k = 0; k < n_in; ++k) {
+            double acc = 0.0;
+            for (int j = 0; j < r; ++j)
+                acc += wload(Bm, dtype, (size_t)o * (size_t)r + (size_t)j) * wload(A, dtype, (size_t)j * (size_t)n_in + (size_t)k);
+            out[(size_t)o * (size_t)n_in + (size_t)k] = wload(W, dtype, (size_t)o * (size_t)n_in + (size_t)k) + scale * acc;
+        }
 }
 
 /* RMSNorm: out[k] = x[k] * g[k] / sqrt(mean_k x[k]^2 + eps) */

@@ -84,6 +84,8 @@ def lib() -> C.CDLL:
                                                C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p,
                                                C.POINTER(C.c_float)]
         L.cqil_set_tuning.argtypes = [C.c_char_p, C.c_int]
+        L.cqil_merge_lora.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
+                                      C.c_void_p]
         L.cqil_model_workspace_bytes.restype = C.c_size_t
         L.cqil_model_workspace_bytes.argtypes = [C.POINTER(cqil_model), C.c_int, C.c_int]
         L.cqil_model_forward.argtypes = [C.POINTER(cqil_model), C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -184,6 +186,18 @@ def cqil_set_tuning(key: str, value: int) -> None:
     rc = lib().cqil_set_tuning(key.encode(), int(value))
     if rc:
         raise CqilError(rc, f"cqil_set_tuning({key}, {value})")
+
+
+def cqil_merge_lora(W: torch.Tensor, A: torch.Tensor, Bm: torch.Tensor, scale: float = 1.0) -> None:
+    """W += scale * Bm @ A in place (W [out,in], A [r,in], Bm [out,r], one dtype, contiguous, on the GPU)."""
+    assert W.dtype == A.dtype == Bm.dtype and W.is_contiguous() and A.is_contiguous() and Bm.is_contiguous()
+    n_out, n_in = W.shape
+    r = A.shape[0]
+    assert A.shape == (r, n_in) and Bm.shape == (n_out, r)
+    rc = lib().cqil_merge_lora(_ptr(W), _ptr(A), _ptr(Bm), CQIL_BF16 if W.dtype == torch.bfloat16 else CQIL_F32, n_out,
+                               n_in, r, float(scale), _stream())
+    if rc:
+        raise CqilError(rc, "cqil_merge_lora")
 
 
 DECODE_KERNELS = ("qkv_rope", "attn_decode", "oproj", "gateup", "down", "merge")

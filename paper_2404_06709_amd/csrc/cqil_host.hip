@@ -217,6 +217,17 @@ static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const 
     return e == hipSuccess ? CQIL_OK : CQIL_EHIP;
 }
 
+int cqil_merge_lora(void* W, const void* A, const void* Bm, int dtype, int n_out, int n_in, int rank, float scale,
+                    void* stream) {
+    if (!W || !A || !Bm) return CQIL_EINVAL;
+    if (dtype != CQIL_F32 && dtype != CQIL_BF16) return CQIL_EINVAL;
+    const int v = dtype == CQIL_BF16 ? 8 : 4;
+    if (n_out < 1 || n_in < v || n_in % v || rank < 1 || rank > 1024) return CQIL_EINVAL;
+    if (!aligned16(W) || !aligned16(A)) return CQIL_EINVAL;
+    return launch_merge_lora(W, A, Bm, dtype, n_out, n_in, rank, scale, (hipStream_t)stream) == hipSuccess ? CQIL_OK
+                                                                                                             : CQIL_EHIP;
+}
+
 int cqil_group_forward(const cqil_dims* dims, int P, int bypass_d, const void* packed, cqil_kv* kv, const void* x_in,
                        void* x_out, int B, int T, int advance_kv_len, void* workspace, size_t workspace_bytes,
                        void* stream) {

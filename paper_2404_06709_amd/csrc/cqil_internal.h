@@ -57,6 +57,9 @@ struct PackArgs {
 hipError_t launch_pack(const cqil_dims& d, int P, const PackArgs& src, char* packed, const cqil_packed_layout& L,
                        hipStream_t st);
 
+hipError_t launch_merge_lora(void* W, const void* A, const void* Bm, int dtype, int n_out, int n_in, int r, float scale,
+                             hipStream_t st);
+
 struct StepArgs {
     cqil_dims d;
     int P, bypass_d, B, T, advance;

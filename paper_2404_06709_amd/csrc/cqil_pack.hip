@@ -131,4 +131,55 @@ hipError_t launch_pack(const cqil_dims& d, int P, const PackArgs& src, char* pac
     return hipGetLastError();
 }
 
+// LoRA merge: W[o][k] += scale * sum_j Bm[o][j] A[j][k], fp32 accumulation, one rounding to the storage type.
+// A thread owns kVec consecutive columns of one row (16-byte accesses); r <= kMaxLoraRank.
+template <typename T>
+__global__ __launch_bounds__(256) void merge_lora_kernel(T* __restrict__ W, const T* __restrict__ A,
+                                                         const T* __restrict__ Bm, int n_out, int n_in, int r,
+                                                         float scale) {
+    constexpr int V = elem<T>::kVec;
+    const int cpr = n_in / V;  // chunks per row
+    const size_t total = (size_t)n_out * cpr;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t o = i / cpr;
+        const int k = (int)(i % cpr) * V;
+        float acc[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[e] = 0.f;
+        for (int j = 0; j < r; ++j) {
+            const float b = elem<T>::load(Bm + o * r + j);
+            float av[V];
+            elem<T>::unpack(load16(A + (size_t)j * n_in + k), av);
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] = fmaf(b, av[e], acc[e]);
+        }
+        float wv[V];
+        elem<T>::unpack(load16(W + o * n_in + k), wv);
+        if constexpr (V == 4) {
+            *reinterpret_cast<float4*>(W + o * n_in + k) =
+                make_float4(wv[0] + scale * acc[0], wv[1] + scale * acc[1], wv[2] + scale * acc[2], wv[3] + scale * acc[3]);
+        } else {
+            uint32_t o32[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                o32[e] = (uint32_t)f32_to_bf16(wv[2 * e] + scale * acc[2 * e]) |
+                         ((uint32_t)f32_to_bf16(wv[2 * e + 1] + scale * acc[2 * e + 1]) << 16);
+            *reinterpret_cast<uint4*>(W + o * n_in + k) = make_uint4(o32[0], o32[1], o32[2], o32[3]);
+        }
+    }
+}
+
+hipError_t launch_merge_lora(void* W, const void* A, const void* Bm, int dtype, int n_out, int n_in, int r, float scale,
+                             hipStream_t st) {
+    const size_t total = (size_t)n_out * (n_in / (dtype == CQIL_BF16 ? 8 : 4));
+    const unsigned grid = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
+    if (dtype == CQIL_BF16)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_lora_kernel<bf16_t>), dim3(grid), dim3(256), 0, st, (bf16_t*)W,
+                           (const bf16_t*)A, (const bf16_t*)Bm, n_out, n_in, r, scale);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_lora_kernel<float>), dim3(grid), dim3(256), 0, st, (float*)W,
+                           (const float*)A, (const float*)Bm, n_out, n_in, r, scale);
+    return hipGetLastError();
+}
+
 }  // namespace cqil

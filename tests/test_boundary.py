@@ -30,6 +30,17 @@ def test_library_exports_every_declared_symbol():
     assert "gfx950" in cq.version()
 
 
+def test_merge_lora_validates_before_launching():
+    L = cq.lib()
+    ok = (0x1000, 0x1000, 0x1000)
+    assert L.cqil_merge_lora(None, 0x1000, 0x1000, cq.CQIL_BF16, 16, 32, 4, 1.0, None) == cq.CQIL_EINVAL
+    assert L.cqil_merge_lora(*ok, 7, 16, 32, 4, 1.0, None) == cq.CQIL_EINVAL            # unknown dtype
+    assert L.cqil_merge_lora(*ok, cq.CQIL_BF16, 16, 36, 4, 1.0, None) == cq.CQIL_EINVAL  # n_in not a multiple of 8
+    assert L.cqil_merge_lora(*ok, cq.CQIL_F32, 16, 32, 0, 1.0, None) == cq.CQIL_EINVAL   # rank
+    assert L.cqil_merge_lora(*ok, cq.CQIL_F32, 16, 32, 2048, 1.0, None) == cq.CQIL_EINVAL
+    assert L.cqil_merge_lora(0x1004, 0x1000, 0x1000, cq.CQIL_F32, 16, 32, 4, 1.0, None) == cq.CQIL_EINVAL  # alignment
+
+
 def test_strerror_covers_all_codes():
     texts = {cq.strerror(c) for c in (0, -1, -2, -3, -4)}
     assert len(texts) == 5 and "unknown" not in " ".join(texts)

@@ -106,6 +106,52 @@ def test_pack_group_is_a_bit_exact_index_map(shape, P, dtype):
         assert (raw[a:b] == 0xAB).all()
 
 
+# ------------------------------------------------------------------------------------------ LoRA merge
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_merge_lora_matches_oracle_and_feeds_the_group(dtype):
+    """W + Bm A at rank 1, 8 and 64 on a non-square matrix (one rounding to the storage type: at most one unit in
+    the last place from the oracle's rounded double sum), then a group step on merged weights against the oracle
+    run on its own merged weights."""
+    gen = synth.generator(71)
+    for r in (1, 8, 64):
+        W = synth.normal((48, 104), 0.05, dtype, gen)
+        A = synth.normal((r, 104), 0.2, dtype, gen)
+        Bm = synth.normal((48, r), 0.2, dtype, gen)
+        ref = orc.merge_lora(synth.to_numpy(W), synth.to_numpy(A), synth.to_numpy(Bm), 1.0)
+        Wg = W.cuda().clone()
+        cq.cqil_merge_lora(Wg, A.cuda(), Bm.cuda(), 1.0)
+        got = synth.widen(Wg.cpu())
+        # rounding bound: one storage rounding of the result plus fp32 roundings of the terms (which may cancel)
+        ulp = 2.0 ** -8 if dtype == torch.bfloat16 else 2.0 ** -23
+        terms = np.abs(synth.widen(W)) + np.abs(synth.widen(Bm)) @ np.abs(synth.widen(A))
+        assert np.all(np.abs(got - ref) <= ulp * np.abs(ref) + 2.0 ** -22 * terms), f"rank {r}"
+        assert np.abs(got - synth.widen(W)).max() > 1e-3                 # the adapter did change the matrix
+    # a whole group: adapters on all seven matrices of two layers
+    P, shape = 2, TINY
+    layers = synth.make_layers(P, shape, dtype, 7100, w_std=0.05, gain_jitter=0.1)
+    merged_gpu, merged_np = [], []
+    for L in layers:
+        Lg = {k: v.cuda().clone() for k, v in L.items()}
+        Ln = dict(synth.layer_to_numpy(L))
+        for name in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown"):
+            n_out, n_in = L[name].shape
+            A = synth.normal((8, n_in), 0.1, dtype, gen)
+            Bm = synth.normal((n_out, 8), 0.1, dtype, gen)
+            cq.cqil_merge_lora(Lg[name], A.cuda(), Bm.cuda(), 1.0)
+            m64 = orc.merge_lora(Ln[name], synth.to_numpy(A), synth.to_numpy(Bm), 1.0)
+            Ln[name] = synth.to_numpy(torch.from_numpy(m64).to(dtype))       # the oracle's own rounding
+        merged_gpu.append(Lg); merged_np.append(Ln)
+    gd, od = gdims(shape, 64, dtype), odims(shape, 64, dtype)
+    group = rt.Group(gd, merged_gpu, b_max=1)
+    x = synth.normal((1, 6, shape.d_model), 1.0, dtype, synth.generator(72))
+    group.set_kv_len([0])
+    y = group.forward(x.cuda(), 1)
+    okc, ovc = orc.new_cache(P, 1, od), orc.new_cache(P, 1, od)
+    ref = orc.group_forward(od, merged_np, 1, okc, ovc, [0], synth.widen(x))
+    # the two sides round a few merged weights differently (ties); that is inside the step tolerance
+    assert rel_err(synth.widen(y.cpu()), ref) <= TOL[dtype]
+
+
 # ------------------------------------------------------------------------------------------ decode, one token
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("shape", [TINY, MID, ODD, WIDE])

@@ -197,6 +197,36 @@ def test_group_forward_matches_eq4_written_with_library_modules(P, d):
     np.testing.assert_allclose(out[0], ref.numpy(), rtol=1e-10, atol=1e-12)
 
 
+# ----------------------------------------------------------------------------- LoRA merge (alpha = rank)
+def test_lora_merge_unit_vectors_touch_one_element():
+    """Bm = e_i (column j0 of the rank axis), A = c e_k^T: only W[i,k] changes, by c.  A transposed operand or a
+    swapped index would move the change elsewhere (the matrix is not square)."""
+    gen = synth.generator(61)
+    W = synth.to_numpy(synth.normal((5, 9), 1.0, torch.float32, gen))
+    A = np.zeros((3, 9), dtype=np.float32); Bm = np.zeros((5, 3), dtype=np.float32)
+    A[1, 7] = 0.25; Bm[4, 1] = 1.0
+    out = orc.merge_lora(W, A, Bm)
+    delta = out - W.astype(np.float64)
+    expect = np.zeros((5, 9)); expect[4, 7] = 0.25
+    np.testing.assert_array_equal(delta, expect)
+    np.testing.assert_array_equal(orc.merge_lora(W, A, np.zeros_like(Bm)), W.astype(np.float64))   # Bm = 0: identity
+    np.testing.assert_array_equal(orc.merge_lora(W, A, Bm, scale=-2.0) - W, -2.0 * expect)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_lora_merged_matrix_acts_as_base_plus_low_rank_path(bf16):
+    """(W + Bm A) x = W x + Bm (A x): the merged weights give what the adapter computes on the side."""
+    gen = synth.generator(62)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    W = synth.to_numpy(synth.normal((24, 40), 0.05, dt, gen))
+    A = synth.to_numpy(synth.normal((4, 40), 0.3, dt, gen))
+    Bm = synth.to_numpy(synth.normal((24, 4), 0.3, dt, gen))
+    x = synth.widen(synth.normal((40,), 1.0, torch.float32, gen))
+    merged = orc.merge_lora(W, A, Bm)
+    side = orc.linear(W, x) + orc.linear(Bm, orc.linear(A, x))
+    np.testing.assert_allclose(merged @ x, side, rtol=1e-12, atol=1e-13)
+
+
 # ----------------------------------------------------------------------------- App. A, Eq.5 (d = -1)
 @pytest.mark.parametrize("P", [1, 3])
 def test_attention_ffn_parallel_form_matches_library_modules(P):
