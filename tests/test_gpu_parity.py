@@ -202,6 +202,50 @@ def test_decode_is_deterministic_and_in_place():
     assert pair.group.kv_len.cpu()[0].item() == 260             # advance=False leaves the length alone
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_group_steps_replay_from_a_hip_graph(dtype):
+    """The library only launches kernels on the caller's stream (no allocation, no synchronisation, no memset):
+    a prefill chunk and four decode steps captured into one graph replay bit for bit, three times, with eager
+    work and synchronisation between the replays."""
+    P, S0 = 2, 20
+    pair = Pair(MID, P, dtype, max_seq=64, b_max=1, seed=31, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([S0], seed=4)
+    g = pair.group
+    k0, v0 = g.k.clone(), g.v.clone()
+    xp = pair.hidden(1, 3, seed=1).cuda()
+    xs = [pair.hidden(1, 1, seed=2 + i).cuda() for i in range(4)]
+
+    def run(outs):
+        g.forward(xp, 1, advance=True, out=outs[0])
+        for i in range(4):
+            g.forward(xs[i], 1, advance=True, out=outs[1 + i])
+
+    def reset():
+        g.k.copy_(k0); g.v.copy_(v0)
+        g.set_kv_len([S0]); g.kv.max_kv_len = S0
+
+    eager = [torch.empty_like(xp)] + [torch.empty_like(x) for x in xs]
+    reset(); run(eager)                                   # also sizes the workspaces before the capture
+    torch.cuda.synchronize()
+    k_e = g.k.clone()
+    outs = [torch.empty_like(t) for t in eager]
+    reset()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(outs)
+    for rep in range(3):
+        for t in outs:
+            t.fill_(float("nan"))
+        reset()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(outs, eager):
+            assert torch.equal(a, b), f"replay {rep}"
+        assert torch.equal(g.k, k_e) and g.kv_len.cpu()[0].item() == S0 + 7
+
+
 # ------------------------------------------------------------------------------------------ prefill / batch
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("shape", [TINY, ODD])
