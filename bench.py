@@ -84,6 +84,72 @@ def prefill(args, cq, rt, synth, torch) -> int:
     return 0
 
 
+def whole_model(args, cq, rt, synth, torch) -> int:
+    """Alg.1 on a LLaMA-33B-shaped decoder: layers 21..60 in groups of four (Sec.4.2), bypass distance 1, against the
+    plain sequential model (every layer a group of one) built from the same weights."""
+    shape, V, L, Tp = synth.SHAPES["33b"], 32000, 60, 512
+    steps = min(args.steps, 128)
+    max_seq = Tp + steps + 8
+    dtype = torch.bfloat16
+    dims = cq.make_dims(shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, max_seq, dtype)
+    sizes = cq.cqil_partition(L, 4, 21, 60)
+    gen = synth.generator(1005, "cuda")
+    grouped, singles = [], []
+    for P in sizes:
+        layers = [synth.make_layer(shape, dtype, gen) for _ in range(P)]
+        g = rt.Group(dims, layers, b_max=1)
+        grouped.append(g)
+        singles.extend([g] if P == 1 else [rt.Group(dims, [Ly], b_max=1) for Ly in layers])
+        torch.cuda.synchronize()
+        del layers
+    emb = synth.normal((V, shape.d_model), 1.0, dtype, gen)
+    head = synth.normal((V, shape.d_model), 0.02, dtype, gen)
+    gfin = torch.ones(shape.d_model, dtype=dtype, device="cuda")
+    tokens0 = torch.randint(0, V, (1, Tp), generator=synth.generator(5)).to(torch.int32).cuda()
+
+    def run(groups):
+        kv_len = torch.zeros(1, dtype=torch.int32, device="cuda")
+        model = cq.Model(dims, [g.P for g in groups], [g.packed for g in groups], [g.k for g in groups],
+                         [g.v for g in groups], kv_len, emb, gfin, head)
+        nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+        ws_p = torch.empty(cq.cqil_model_workspace_bytes(model, 1, Tp), dtype=torch.uint8, device="cuda")
+        ws_d = torch.empty(cq.cqil_model_workspace_bytes(model, 1, 1), dtype=torch.uint8, device="cuda")
+        out = {}
+        for rep in range(2):                     # first pass warms up, second is timed
+            kv_len.zero_(); model.c.max_kv_len = 0
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            cq.cqil_model_forward(model, tokens0, 1, Tp, args.bypass, True, None, None, nxt, ws_p)
+            torch.cuda.synchronize(); out["prefill_ms"] = (time.perf_counter() - t0) * 1e3
+            tok = nxt.reshape(1, 1).clone()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                cq.cqil_model_forward(model, tok, 1, 1, args.bypass, True, None, None, nxt, ws_d)
+                tok.copy_(nxt.reshape(1, 1))     # greedy feedback stays on the device
+            torch.cuda.synchronize(); out["decode_ms"] = (time.perf_counter() - t0) * 1e3 / steps
+        return out
+
+    cqil, seq = run(grouped), run(singles)
+    dm, f = shape.d_model, shape.d_ffn
+    layer_bytes = (4 * dm * dm + 3 * dm * f) * 2
+    kv_bytes = L * 2 * (Tp + steps / 2) * dm * 2
+    token_bytes = L * layer_bytes + V * dm * 2 + kv_bytes
+    gbps = token_bytes / (cqil["decode_ms"] * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "decode_ms_per_token_whole_model", "value": round(cqil["decode_ms"], 3), "unit": "ms/token",
+        "n_gpus": 1, "steps": steps, "warmup": steps, "ms_per_step": round(cqil["decode_ms"], 3),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"llama33b_shape_model_L60_p4_s21_e60_prefill{Tp}_decode{steps}", "groups": sizes,
+                   "bypass_d": args.bypass, "vocab": V},
+        "tokens_per_s": round(1e3 / cqil["decode_ms"], 1), "prefill_ms": round(cqil["prefill_ms"], 2),
+        "sequential_ms_per_token": round(seq["decode_ms"], 3), "sequential_prefill_ms": round(seq["prefill_ms"], 2),
+        "decode_latency_reduction": round(1.0 - cqil["decode_ms"] / seq["decode_ms"], 4),
+        "prefill_latency_reduction": round(1.0 - cqil["prefill_ms"] / seq["prefill_ms"], 4),
+        "roofline": {"bound": "hbm", "kernel": "whole token", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+    }))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,6 +165,9 @@ def main() -> int:
     ap.add_argument("--prefill", type=int, default=0, metavar="T",
                     help="time one token-parallel group step over --batch sequences of T new tokens (empty caches) "
                          "instead of decode steps; reports TFLOP/s against the bf16 matrix-core peak")
+    ap.add_argument("--model", action="store_true",
+                    help="whole LLaMA-33B-shaped model (60 layers, vocabulary 32000): 512-token prefill, then greedy "
+                         "decode steps with the partition (p=4, s=21, e=60), against the same layers run one by one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=4)
@@ -121,6 +190,8 @@ def main() -> int:
     dev = "cuda"
     if args.prefill > 0:
         return prefill(args, cq, rt, synth, torch)
+    if args.model:
+        return whole_model(args, cq, rt, synth, torch)
     shape = synth.SHAPES[args.shape]
     P, d_byp = args.P, args.bypass
     dtype = torch.bfloat16

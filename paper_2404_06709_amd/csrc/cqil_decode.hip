@@ -259,11 +259,18 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     const int bd = s.bypass_d >= P ? P - 1 : s.bypass_d;
     constexpr int KB = tile<T>::KB;
     const int K = P * f, Kp = (K + KB - 1) / KB * KB;
-    // k splits measured on 7B/13B/33B-shaped groups: narrow models want fewer, fatter workgroups
+    // k splits, from measurements on 7B/13B/33B-shaped groups of 1, 2 and 4 layers: a kernel wants a certain number
+    // of waves in total (units x P x split), so small groups split deeper; narrow models (short rows, where the
+    // per-workgroup prologue weighs more) want fewer, fatter workgroups in the O, gate/up and down kernels.
     const bool narrow = dm <= 4096;
-    const int ks_q = g_tune.ksplit_qkv ? g_tune.ksplit_qkv : 4;
-    const int ks_o = g_tune.ksplit_o ? g_tune.ksplit_o : (narrow ? 2 : 1);
-    const int ks_g = g_tune.ksplit_gu ? g_tune.ksplit_gu : (narrow ? 2 : 4);
+    auto split_for = [](long units, long want_waves) {
+        int ks = 1;
+        while (ks < 8 && units * ks < want_waves) ks *= 2;
+        return ks;
+    };
+    const int ks_q = g_tune.ksplit_qkv ? g_tune.ksplit_qkv : split_for(3L * nh * (dk / 32) * P, 8192);
+    const int ks_o = g_tune.ksplit_o ? g_tune.ksplit_o : (narrow ? (P >= 4 ? 2 : 8) : (P >= 4 ? 1 : (P >= 2 ? 2 : 4)));
+    const int ks_g = g_tune.ksplit_gu ? g_tune.ksplit_gu : (narrow ? ((P == 2 || P == 3) ? 4 : 2) : split_for((long)(f / kGuBlock) * P, 16384));
     const size_t lds_x = ((size_t)dm + kRedFloats + 16) * sizeof(float);
 
     // optional per-kernel timing: event i is recorded before kernel i, the last event after the last kernel
@@ -303,7 +310,9 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     }
     CQIL_MARK(4);
     {
-        const int ks_d = g_tune.ksplit_d ? g_tune.ksplit_d : (narrow ? 1 : 4);
+        const int ks_d = g_tune.ksplit_d ? g_tune.ksplit_d
+                                         : (narrow ? (P >= 4 ? 1 : (P >= 2 ? 2 : 4))
+                                                   : split_for((long)(dm / 16) * s.wl.n_slices, 16384));
         const int units = dm / 16, uw = kWaves / ks_d;
         hipLaunchKernelGGL(HIP_KERNEL_NAME(down_kernel<T>), dim3((units + uw - 1) / uw, s.wl.n_slices), dim3(kThreads),
                            ((size_t)s.wl.down_slice + kRedFloats) * sizeof(float), st, u, wdown, dpart, K, Kp, dm,
