@@ -11,12 +11,14 @@ constexpr int kWave = 64;
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// round-to-nearest-even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// round-to-nearest-even; NaN stays NaN.  The casts compile to v_cvt_pk_bf16_f32 on gfx950.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two values -> one dword (a in the low half)
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float a, float b) {
+    typedef float cvt_f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 cvt_bf16x2 __attribute__((ext_vector_type(2)));
+    const cvt_f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, cvt_bf16x2));
 }
 
 template <typename T> struct elem;

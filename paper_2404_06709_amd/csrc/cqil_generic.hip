@@ -27,10 +27,10 @@ __device__ __forceinline__ uint4 pack16(const float (&f)[4], const float*) {
     return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
 }
 __device__ __forceinline__ uint4 pack16(const float (&f)[8], const bf16_t*) {
-    return make_uint4((uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16),
-                      (uint32_t)f32_to_bf16(f[2]) | ((uint32_t)f32_to_bf16(f[3]) << 16),
-                      (uint32_t)f32_to_bf16(f[4]) | ((uint32_t)f32_to_bf16(f[5]) << 16),
-                      (uint32_t)f32_to_bf16(f[6]) | ((uint32_t)f32_to_bf16(f[7]) << 16));
+    return make_uint4(f32x2_to_bf16x2(f[0], f[1]),
+                      f32x2_to_bf16x2(f[2], f[3]),
+                      f32x2_to_bf16x2(f[4], f[5]),
+                      f32x2_to_bf16x2(f[6], f[7]));
 }
 
 // nrm[l][m][k] = x[m][k] * rsqrt(mean x[m]^2 + eps) * g[l][k]; one workgroup per token row, 16-byte accesses

@@ -27,7 +27,7 @@ typedef float attn_f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kPfBQ = 128, kPfBKV = 64, kPfThreads = 256;
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-    return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+    return f32x2_to_bf16x2(a, b);
 }
 
 template <int DK>

@@ -33,8 +33,8 @@ constexpr int kEpiNone = 0, kEpiAddR = 1, kEpiSwiglu = 2;
 
 __device__ __forceinline__ void gemm_store4(bf16_t* p, const float (&v)[4]) {
     uint2 o;
-    o.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-    o.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+    o.x = f32x2_to_bf16x2(v[0], v[1]);
+    o.y = f32x2_to_bf16x2(v[2], v[3]);
     *reinterpret_cast<uint2*>(p) = o;
 }
 __device__ __forceinline__ void gemm_store4(float* p, const float (&v)[4]) {

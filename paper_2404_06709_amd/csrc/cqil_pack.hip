@@ -162,8 +162,7 @@ __global__ __launch_bounds__(256) void merge_lora_kernel(T* __restrict__ W, cons
             uint32_t o32[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                o32[e] = (uint32_t)f32_to_bf16(wv[2 * e] + scale * acc[2 * e]) |
-                         ((uint32_t)f32_to_bf16(wv[2 * e + 1] + scale * acc[2 * e + 1]) << 16);
+                o32[e] = f32x2_to_bf16x2(wv[2 * e] + scale * acc[2 * e], wv[2 * e + 1] + scale * acc[2 * e + 1]);
             *reinterpret_cast<uint4*>(W + o * n_in + k) = make_uint4(o32[0], o32[1], o32[2], o32[3]);
         }
     }
