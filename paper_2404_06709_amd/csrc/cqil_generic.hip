@@ -35,7 +35,7 @@ __device__ __forceinline__ uint4 pack16(const float (&f)[8], const bf16_t*) {
 
 // nrm[l][m][k] = x[m][k] * rsqrt(mean x[m]^2 + eps) * g[l][k]; one workgroup per token row, 16-byte accesses
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_multi_kernel(const T* __restrict__ x, const T* __restrict__ g,
+__global__ __launch_bounds__(1024) void rmsnorm_multi_kernel(const T* __restrict__ x, const T* __restrict__ g,
                                                             T* __restrict__ nrm, int P, int M, int d_model, float eps) {
     constexpr int V = elem<T>::kVec;
     __shared__ float scratch[16];
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void rmsnorm_multi_kernel(const T* __restrict_
     const T* xr = x + (size_t)m * d_model;
     const int n_chunks = d_model / V;
     float ss = 0.f;
-    for (int c = tid; c < n_chunks; c += 256) {
+    for (int c = tid; c < n_chunks; c += blockDim.x) {
         float v[V];
         elem<T>::unpack(load16(xr + c * V), v);
 #pragma unroll
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void rmsnorm_multi_kernel(const T* __restrict_
     }
     ss = block_sum(ss, scratch);
     const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
-    for (int c = tid; c < n_chunks; c += 256) {
+    for (int c = tid; c < n_chunks; c += blockDim.x) {
         float v[V];
         elem<T>::unpack(load16(xr + c * V), v);
         for (int l = 0; l < P; ++l) {
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void rmsnorm_multi_kernel(const T* __restrict_
 // Rotary embedding of q (in place) and k, and the KV append, for one token row per workgroup.  A unit is
 // (layer, head, chunk of kVec rotary pairs): 16-byte accesses on both halves of the head (d_k / 2 % kVec == 0).
 template <typename T>
-__global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, const float2* __restrict__ rope,
+__global__ __launch_bounds__(1024) void rope_append_kernel(T* __restrict__ qkv, const float2* __restrict__ rope,
                                                           const int32_t* __restrict__ kv_len, T* __restrict__ kc,
                                                           T* __restrict__ vc, int P, int T_new, int n_heads, int d_k,
                                                           int max_seq, int b_max) {
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, c
     if (pos < 0 || pos >= max_seq) return;
     const size_t d_model = (size_t)n_heads * d_k;
     const int units = P * n_heads * cph;
-    for (int u = threadIdx.x; u < units; u += 256) {
+    for (int u = threadIdx.x; u < units; u += blockDim.x) {
         const int c = u % cph, lh = u / cph, h = lh % n_heads, l = lh / n_heads;
         const int i = c * V;
         T* row = qkv + (size_t)m * P * 3 * d_model + (size_t)l * 3 * d_model + (size_t)h * d_k;
@@ -205,10 +205,11 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
 //   h_i = x + sum_{j=max(0,i-d)}^{i} a_j ; nrm_i = RMSNorm(h_i) g_i ; resid = x + sum_j a_j
 // 16-byte accesses: a thread owns chunks of kVec consecutive elements (d_model % kVec == 0).
 template <typename T>
-__global__ __launch_bounds__(256) void bypass_norm_kernel(const T* __restrict__ x, const float* __restrict__ a,
+__global__ __launch_bounds__(1024) void bypass_norm_kernel(const T* __restrict__ x, const float* __restrict__ a,
                                                           const T* __restrict__ g_ffn, T* __restrict__ nrm,
                                                           float* __restrict__ resid, int P, int bypass_d, int M,
-                                                          int d_model, float eps) {
+                                                          int d_model, float eps, int32_t* __restrict__ kv_len,
+                                                          int advance_B, int advance_T) {
     constexpr int V = elem<T>::kVec;
     __shared__ float scratch[16];
     const int m = blockIdx.x, tid = threadIdx.x;
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(256) void bypass_norm_kernel(const T* __restrict__ 
     for (int i = 0; i < P; ++i) {
         const int jlo = bypass_d < 0 ? i + 1 : max(0, i - bypass_d);  // negative: Eq.5, the input is x alone
         float ss = 0.f;
-        for (int c = tid; c < n_chunks; c += 256) {
+        for (int c = tid; c < n_chunks; c += blockDim.x) {
             float hv[V];
             window(c * V, jlo, i, hv);
 #pragma unroll
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(256) void bypass_norm_kernel(const T* __restrict__ 
         const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
         const T* gi = g_ffn + (size_t)i * d_model;
         T* out = nrm + ((size_t)i * M + m) * d_model;
-        for (int c = tid; c < n_chunks; c += 256) {
+        for (int c = tid; c < n_chunks; c += blockDim.x) {
             float hv[V], gv[V];
             window(c * V, jlo, i, hv);
             elem<T>::unpack(load16(gi + c * V), gv);
@@ -248,7 +249,10 @@ __global__ __launch_bounds__(256) void bypass_norm_kernel(const T* __restrict__ 
             *reinterpret_cast<uint4*>(out + c * V) = pack16(hv, (const T*)nullptr);
         }
     }
-    for (int c = tid; c < n_chunks; c += 256) {
+    // every reader of the cache lengths (rotary/append, attention) ran before this kernel: advance them here
+    if (advance_B > 0 && m == 0)
+        for (int b = tid; b < advance_B; b += blockDim.x) kv_len[b] += advance_T;
+    for (int c = tid; c < n_chunks; c += blockDim.x) {
         float hv[V];
         window(c * V, 0, P - 1, hv);
 #pragma unroll
@@ -394,13 +398,14 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     const int bd = s.bypass_d >= P ? P - 1 : s.bypass_d;
     const size_t Mdm = (size_t)M * dm;
 
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(rmsnorm_multi_kernel<T>), dim3(M), dim3(256), 0, st, x, g_attn, nrm, P, M, dm,
-                       d.rms_eps);
+    const int row_threads = M <= 64 ? 1024 : 256;  // few rows: more threads per row, the kernels are latency-bound
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(rmsnorm_multi_kernel<T>), dim3(M), dim3(row_threads), 0, st, x, g_attn, nrm, P, M,
+                       dm, d.rms_eps);
     hipError_t ge;
     float* part = s.wl.gemm_part_floats ? (float*)(s.ws + s.wl.gemm_part) : nullptr;
     if ((ge = gemm_any<T, T, false>(nrm, wqkv, qkv, nullptr, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm,
                             (size_t)3 * dm, 0, (size_t)3 * dm, st, part, s.wl.gemm_part_floats)) != hipSuccess) return ge;
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M), dim3(256), 0, st,
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M), dim3(row_threads), 0, st,
                        qkv, rope, s.kv_len, (T*)s.kc, (T*)s.vc, P, s.T, nh, dk, d.max_seq, s.b_max);
     const int lps = dk * (int)sizeof(T) / 16;
     bool attn_done = false;
@@ -457,8 +462,8 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     }
     if ((ge = gemm_any<T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, 0, (size_t)dm, Mdm, st,
                                         part, s.wl.gemm_part_floats)) != hipSuccess) return ge;
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(256), 0, st, x, a, g_ffn, nrm, resid, P, bd,
-                       M, dm, d.rms_eps);
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(row_threads), 0, st, x, a, g_ffn, nrm, resid,
+                       P, bd, M, dm, d.rms_eps, s.kv_len, s.advance ? s.B : 0, s.T);
     if constexpr (std::is_same<T, bf16_t>::value) {
         // gate/up product with SwiGLU in the epilogue: u is written directly, gate and up never reach memory
         if ((ge = gemm_mfma<bf16_t, kEpiSwiglu>(g_tune.gemm_tile, nrm, wgu, u, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * f,
@@ -476,7 +481,6 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
         if ((ge = gemm_any<T, T, true>(u, wdown, (T*)s.x_out, resid, M, dm, P * f, (size_t)P * f, Kp, dm, 1, 0, 0, 0, 0, st, part,
                                        s.wl.gemm_part_floats)) != hipSuccess) return ge;
     }
-    if (s.advance) hipLaunchKernelGGL(advance_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st, s.kv_len, s.B, s.T);
     return hipGetLastError();
 }
 
