@@ -8,8 +8,8 @@
 // half of it).  The weight rows are its A operand (lane i + 32 gg holds row i, columns 8 gg .. 8 gg + 7 of a
 // 16-column slab), the tokens its B operand, so a lane ends up with groups of 4 consecutive weight rows of one
 // token: 4 consecutive elements of a C row.
-// A workgroup of WM x WN waves owns 128 WM tokens x 64 WN weight rows; a wave owns 128 tokens x 64 weight rows =
-// 4 x 2 instruction tiles (128 accumulator registers).
+// A workgroup of WM x WN waves owns 32 TT WM tokens x 64 WN weight rows; a wave owns 32 TT tokens x 64 weight rows
+// = TT x 2 instruction tiles (TT = 4: 128 accumulator registers; TT = 1 for up to 32 token rows).
 // Weights never touch LDS: the packed layout stores every 16-row x 32-column tile in [column group][row] order,
 // so the fragment of 32 rows x 16 columns is four contiguous 256-byte runs of two vertically adjacent tiles,
 // which a wave reads straight from global memory, one 32-column slab ahead of use.
@@ -44,12 +44,12 @@ __device__ __forceinline__ void gemm_store4(float* p, const float (&v)[4]) {
 // N, K: logical sizes of this group's product; N % 4 == 0, K % 8 == 0, M >= 1.  strip_step / ktile_step: group
 // strides in 16-row strips / 32-column tiles inside W.  R (kEpiAddR): fp32 [M][N] added to the result.
 // kEpiSwiglu: N % 32 == 0 rows as blocks of 16 gate + 16 up rows; C gets N / 2 columns per group.
-template <typename CT, int EPI, int WM, int WN>
+template <typename CT, int EPI, int WM, int WN, int TT>
 __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, CT* __restrict__ C, const float* __restrict__ R, int M,
     int N, int K, size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t strip_step, size_t ktile_step,
     size_t sC, int ksplit, float* __restrict__ part) {
-    constexpr int BM = 128 * WM, BN = 64 * WN, NT = 64 * WM * WN;
+    constexpr int BM = 32 * TT * WM, BN = 64 * WN, NT = 64 * WM * WN;
     constexpr int TE = 512;            // elements per tile
     constexpr int STAGE = BM * 64;     // activation elements per LDS stage
     constexpr int APT = BM * 8 / NT;   // activation pieces per thread and step
@@ -123,9 +123,9 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
                 make_uint4(areg[q].x & a_keep, areg[q].y & a_keep, areg[q].z & a_keep, areg[q].w & a_keep);
     };
 
-    gemm_f32x16 acc[4][2];
+    gemm_f32x16 acc[TT][2];
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < TT; ++t)
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
@@ -134,14 +134,14 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     // activation fragment of token tile t, slab k16 of the step: tile (4 wm + t) * 4 + k16, slot (j + 2 k16 + gg) mod 32
     int frag[4];
 #pragma unroll
-    for (int k16 = 0; k16 < 4; ++k16) frag[k16] = (4 * wm * 4 + k16) * TE + (fgg * 32 + ((fi + 2 * k16 + fgg) & 31)) * 8;
-    auto read_af = [&](uint4(&af)[4], const bf16_t* as, int k16) {
+    for (int k16 = 0; k16 < 4; ++k16) frag[k16] = (TT * wm * 4 + k16) * TE + (fgg * 32 + ((fi + 2 * k16 + fgg) & 31)) * 8;
+    auto read_af = [&](uint4(&af)[TT], const bf16_t* as, int k16) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) af[t] = *reinterpret_cast<const uint4*>(as + frag[k16] + t * 4 * TE);
+        for (int t = 0; t < TT; ++t) af[t] = *reinterpret_cast<const uint4*>(as + frag[k16] + t * 4 * TE);
     };
-    auto mma = [&](const uint4(&af)[4], int b) {
+    auto mma = [&](const uint4(&af)[TT], int b) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < TT; ++t)
 #pragma unroll
             for (int s = 0; s < 2; ++s)
                 acc[t][s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(gemm_bf16x8, wf[b][s]),
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     // and the next step's activations are written to the other LDS stage before the third slab's instructions, so
     // that the single barrier of a step is passed while those are in the pipe.  The scheduling barriers keep the
     // compiler from undoing the order.
-    uint4 afa[4], afb[4];
+    uint4 afa[TT], afb[TT];
     const int steps_per_slice = (n_steps + ksplit - 1) / ksplit;
     const int s_beg = ks * steps_per_slice, s_end = min(s_beg + steps_per_slice, n_steps);  // may be empty
     load_a(s_beg);
@@ -195,8 +195,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     if (ksplit > 1) {  // partial sums of this K slice: part[ks][z][m][n], fp32; gemm_reduce_kernel finishes
         float* pz = part + ((size_t)ks * groups + z) * (size_t)M * N;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int m = m0 + 128 * wm + 32 * t + fi;
+        for (int t = 0; t < TT; ++t) {
+            const int m = m0 + 32 * TT * wm + 32 * t + fi;
             if (m >= M) continue;
 #pragma unroll
             for (int s = 0; s < 2; ++s)
@@ -211,8 +211,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
         return;
     }
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int m = m0 + 128 * wm + 32 * t + fi;
+    for (int t = 0; t < TT; ++t) {
+        const int m = m0 + 32 * TT * wm + 32 * t + fi;
         if (m >= M) continue;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -275,12 +275,15 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
 // in weight rows / columns (multiples of 16 / 32).  part / part_floats: scratch for split-K partial sums (may be
 // null / 0): when the tile grid is too small to fill the chip, K is cut into slices of whole 64-column steps,
 // each slice writes fp32 partial sums and a second kernel adds them in slice order (deterministic).
-template <typename CT, int EPI, int WM, int WN>
+template <typename CT, int EPI, int WM, int WN, int TT>
 static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K,
                                    size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step,
                                    size_t k_step, size_t sC, float* part, size_t part_floats, hipStream_t st) {
-    constexpr int BM = 128 * WM, BN = 64 * WN;
-    constexpr size_t lds_bytes = 2 * (size_t)BM * 64 * 2;
+    constexpr int BM = 32 * TT * WM, BN = 64 * WN;
+    // TT == 1 needs 8 KiB but asks for 64: that keeps two workgroups per CU.  With more resident per CU the
+    // dispatcher packs a grid of a few hundred workgroups onto a part of the chip (measured: CUs busy 60 % of the
+    // kernel, 260 us against 187 us for the 13B gate/up product with 8 rows).
+    constexpr size_t lds_bytes = TT == 1 ? 65536 : 2 * (size_t)BM * 64 * 2;
     constexpr int SN = 8, SM = (WM * WN == 8) ? 4 : 8;
     const int nx = (N + BN - 1) / BN, ny = (M + BM - 1) / BM;
     int ksplit = 1;
@@ -295,7 +298,7 @@ static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, cons
     const long supers = (long)groups * ksplit * ((nx + SN - 1) / SN) * ((ny + SM - 1) / SM);
     const long wgs = (supers + 7) / 8 * 8 * SM * SN;
     if (wgs > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, EPI, WM, WN>), dim3((unsigned)wgs), dim3(64 * WM * WN),
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, EPI, WM, WN, TT>), dim3((unsigned)wgs), dim3(64 * WM * WN),
                        lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16, k_step / 32, sC, ksplit,
                        part);
     if (ksplit > 1) {
@@ -314,10 +317,15 @@ static hipError_t gemm_mfma(int tile_sel, const bf16_t* A, const bf16_t* W, CT* 
                             size_t sC, hipStream_t st, float* part = nullptr, size_t part_floats = 0) {
     if (M < 1 || (N & 3) || (K & 7) || K < 8) return hipErrorInvalidValue;
     // default: 128 x 256 (two workgroups per CU overlap each other's barriers and load latency)
+    // up to 32 token rows (a batch of decode rows): one 32-token tile per wave, a quarter of the matrix-core and LDS
+    // work per weight byte streamed
+    if (M <= 32)
+        return gemm_mfma_launch<CT, EPI, 1, 4, 1>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, part,
+                                                  part_floats, st);
     if (tile_sel == 1)
-        return gemm_mfma_launch<CT, EPI, 2, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, part,
+        return gemm_mfma_launch<CT, EPI, 2, 4, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, part,
                                                part_floats, st);
-    return gemm_mfma_launch<CT, EPI, 1, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, part,
+    return gemm_mfma_launch<CT, EPI, 1, 4, 4>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, part,
                                            part_floats, st);
 }
 
