@@ -163,3 +163,13 @@ def test_model_forward_validates_before_launching():
     assert lib.cqil_model_forward(C.byref(m), 0x1000, 1, 4, -2, 0, None, None, None, 0x1000, need, None) == cq.CQIL_EINVAL
     gs[1] = 0
     assert lib.cqil_model_workspace_bytes(C.byref(m), 1, 4) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus N with N > 1 exits with a message, before touching any device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
