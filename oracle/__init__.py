@@ -132,6 +132,15 @@ def merge_lora(W: np.ndarray, A: np.ndarray, Bm: np.ndarray, scale: float = 1.0)
     return out
 
 
+def input_similarity(X) -> np.ndarray:
+    """Sec.3.1: X [L, M, n] layer inputs for the same M tokens -> [L, L] mean per-token cosine similarity."""
+    X = _f64(X)
+    L, M, n = X.shape
+    sim = np.empty((L, L), dtype=np.float64)
+    lib().orc_input_similarity(_p(X), L, M, n, _p(sim))
+    return sim
+
+
 def rmsnorm(x, g: np.ndarray, eps: float) -> np.ndarray:
     x = _f64(x)
     g = np.ascontiguousarray(g)

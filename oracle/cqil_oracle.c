@@ -15,6 +15,7 @@
  *   orc_attn_module   Eq.2: ATTN(x) = MHA(Norm(x)), heads, softmax(QK^T/sqrt(d_k))V, Concat(...)W^O
  *   orc_ffn_module    Eq.2: FFN(x) = W_2 f(W_1 Norm(x)), instantiated as LLaMA's bias-free SwiGLU
  *   orc_seq_layer     Eq.1: x_{l+1} = x_l + ATTN_l(x_l) + FFN_l(x_l + ATTN_l(x_l))
+ *   orc_input_similarity   mean cosine similarity between the inputs of two layers (Sec.3.1)
  *   orc_merge_lora    W + BA, the merged form of the LoRA adapters the paper fine-tunes (Sec.5.1, App. C)
  *   orc_group_forward Eq.3 (d = 0) and Eq.4 (bypass distance d), Alg.1's middle loop
  *   orc_partition     Sec.4.2 "Layer Partition and Parallelism": (p, s, e) -> group sizes
@@ -98,6 +99,24 @@ void orc_merge_lora(const void *W, const void *A, const void *Bm, int dtype, int
             for (int j = 0; j < r; ++j)
                 acc += wload(Bm, dtype, (size_t)o * (size_t)r + (size_t)j) * wload(A, dtype, (size_t)j * (size_t)n_in + (size_t)k);
             out[(size_t)o * (size_t)n_in + (size_t)k] = wload(W, dtype, (size_t)o * (size_t)n_in + (size_t)k) + scale * acc;
+        }
+}
+
+/* Similarity of layer inputs (Sec.3.1): X [L][M][n] holds the inputs x_l of L layers for the same M tokens;
+ *   sim[a][b] = (1/M) sum_m  <x_a[m], x_b[m]> / (|x_a[m]| |x_b[m]|)
+ * (cosine per token, mean over tokens; a zero vector gives cosine 0). */
+void orc_input_similarity(const double *X, int L, int M, int n, double *sim) {
+    for (int a = 0; a < L; ++a)
+        for (int b = 0; b < L; ++b) {
+            double acc = 0.0;
+            for (int m = 0; m < M; ++m) {
+                const double *xa = X + ((size_t)a * (size_t)M + (size_t)m) * (size_t)n;
+                const double *xb = X + ((size_t)b * (size_t)M + (size_t)m) * (size_t)n;
+                double dot = 0.0, na = 0.0, nb = 0.0;
+                for (int k = 0; k < n; ++k) { dot += xa[k] * xb[k]; na += xa[k] * xa[k]; nb += xb[k] * xb[k]; }
+                if (na > 0.0 && nb > 0.0) acc += dot / (sqrt(na) * sqrt(nb));
+            }
+            sim[(size_t)a * (size_t)L + (size_t)b] = acc / (double)M;
         }
 }
 

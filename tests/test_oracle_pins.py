@@ -197,6 +197,35 @@ def test_group_forward_matches_eq4_written_with_library_modules(P, d):
     np.testing.assert_allclose(out[0], ref.numpy(), rtol=1e-10, atol=1e-12)
 
 
+# ----------------------------------------------------------------------------- Sec.3.1 input similarity
+def test_input_similarity_textbook_cases():
+    """Per-token cosine, mean over tokens: equal directions 1, opposite -1, orthogonal 0, scale-free, symmetric,
+    and a hand-computed 45-degree pair; a mean over vectors instead of over cosines would fail the last check."""
+    n = 8
+    e0 = np.zeros(n); e0[0] = 1.0
+    e1 = np.zeros(n); e1[1] = 1.0
+    X = np.stack([
+        np.stack([e0, e1]),                    # layer 0
+        np.stack([3.0 * e0, -2.0 * e1]),       # layer 1: same direction, opposite direction
+        np.stack([e1, e0 + e1]),               # layer 2: orthogonal, 45 degrees
+    ])
+    sim = orc.input_similarity(X)
+    np.testing.assert_allclose(np.diag(sim), 1.0, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(sim, sim.T, rtol=0, atol=0)
+    assert abs(sim[0, 1] - 0.0) < 1e-15                    # (1 + (-1)) / 2
+    assert abs(sim[0, 2] - (0.0 + np.sqrt(0.5)) / 2) < 1e-15
+    assert abs(sim[1, 2] - (0.0 - np.sqrt(0.5)) / 2) < 1e-15
+    # scale invariance and agreement with the library routine on random data
+    gen = synth.generator(91)
+    Y = synth.widen(synth.normal((4, 5, 24), 1.0, torch.float32, gen))
+    s1 = orc.input_similarity(Y)
+    s2 = orc.input_similarity(Y * np.array([1.0, 7.0, 0.25, 3.0])[:, None, None])
+    np.testing.assert_allclose(s1, s2, rtol=1e-13, atol=1e-14)
+    t = torch.from_numpy(Y)
+    ref = F.cosine_similarity(t[:, None], t[None, :], dim=-1).mean(dim=-1)
+    np.testing.assert_allclose(s1, ref.numpy(), rtol=1e-12, atol=1e-13)
+
+
 # ----------------------------------------------------------------------------- LoRA merge (alpha = rank)
 def test_lora_merge_unit_vectors_touch_one_element():
     """Bm = e_i (column j0 of the rank axis), A = c e_k^T: only W[i,k] changes, by c.  A transposed operand or a
