@@ -130,6 +130,16 @@ int cqil_pack_group(const cqil_dims *dims, int P, const cqil_layer *layers /* ho
 int cqil_merge_lora(void *W, const void *A, const void *Bm, int dtype, int n_out, int n_in, int rank, float scale,
                     void *stream);
 
+/* Similarity of layer inputs (Sec.3.1, the measurement that motivates which layers to group): X (device)
+ * [L][M][n] of `dtype` holds the inputs x_l of L layers for the same M tokens (captured by the caller, e.g. by
+ * running the model as groups of one); sim (device, fp32 [L][L]) receives the mean over tokens of the per-token
+ * cosine <x_a, x_b> / (|x_a| |x_b|) (0 for a zero vector).  workspace: cqil_input_similarity_workspace_bytes(L, M)
+ * bytes (0 for invalid arguments).  1 <= L <= 1024, n a multiple of 16 / sizeof(dtype), X 16-byte aligned;
+ * otherwise CQIL_EINVAL; a short workspace is CQIL_ESIZE.  Deterministic; asynchronous on `stream`. */
+size_t cqil_input_similarity_workspace_bytes(int L, int M);
+int cqil_input_similarity(const void *X, int dtype, int L, int M, int n, float *sim, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
 /* One group step (Eq.4; Eq.3 when bypass_d == 0; Eq.1 when P == 1):
  *   attn_i = ATTN_i(x)                                   i = 0..P-1, all from the same x
  *   h_i    = x + attn_i + sum_{j : 1 <= i-j <= d} attn_j

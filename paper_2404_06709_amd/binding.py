@@ -84,6 +84,10 @@ def lib() -> C.CDLL:
                                                C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p,
                                                C.POINTER(C.c_float)]
         L.cqil_set_tuning.argtypes = [C.c_char_p, C.c_int]
+        L.cqil_input_similarity_workspace_bytes.restype = C.c_size_t
+        L.cqil_input_similarity_workspace_bytes.argtypes = [C.c_int, C.c_int]
+        L.cqil_input_similarity.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                            C.c_size_t, C.c_void_p]
         L.cqil_merge_lora.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
                                       C.c_void_p]
         L.cqil_model_workspace_bytes.restype = C.c_size_t
@@ -186,6 +190,20 @@ def cqil_set_tuning(key: str, value: int) -> None:
     rc = lib().cqil_set_tuning(key.encode(), int(value))
     if rc:
         raise CqilError(rc, f"cqil_set_tuning({key}, {value})")
+
+
+def cqil_input_similarity(X: torch.Tensor) -> torch.Tensor:
+    """X [L, M, n] (bf16 or fp32, contiguous, on the GPU) -> fp32 [L, L] mean per-token cosine similarity (Sec.3.1)."""
+    assert X.dim() == 3 and X.is_contiguous()
+    L_, M, n = X.shape
+    sim = torch.empty(L_, L_, dtype=torch.float32, device=X.device)
+    nbytes = int(lib().cqil_input_similarity_workspace_bytes(L_, M))
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=X.device)
+    rc = lib().cqil_input_similarity(_ptr(X), CQIL_BF16 if X.dtype == torch.bfloat16 else CQIL_F32, L_, M, n, _ptr(sim),
+                                     _ptr(ws), nbytes, _stream())
+    if rc:
+        raise CqilError(rc, "cqil_input_similarity")
+    return sim
 
 
 def cqil_merge_lora(W: torch.Tensor, A: torch.Tensor, Bm: torch.Tensor, scale: float = 1.0) -> None:

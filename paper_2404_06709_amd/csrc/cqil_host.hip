@@ -217,6 +217,38 @@ static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const 
     return e == hipSuccess ? CQIL_OK : CQIL_EHIP;
 }
 
+// chunks of tokens of the similarity kernels: enough workgroups to fill the chip, at least 4 tokens each
+static void similarity_chunks(int L, int M, int* chunks, int* per) {
+    const long pairs = (long)L * (L + 1) / 2;
+    long c = (2048 + pairs - 1) / pairs;
+    if (c > (M + 3) / 4) c = (M + 3) / 4;
+    if (c < 1) c = 1;
+    *per = (int)((M + c - 1) / c);
+    *chunks = (M + *per - 1) / *per;
+}
+
+size_t cqil_input_similarity_workspace_bytes(int L, int M) {
+    if (L < 1 || L > 1024 || M < 1) return 0;
+    int chunks, per;
+    similarity_chunks(L, M, &chunks, &per);
+    return (size_t)chunks * L * L * sizeof(float);
+}
+
+int cqil_input_similarity(const void* X, int dtype, int L, int M, int n, float* sim, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+    if (!X || !sim || !workspace) return CQIL_EINVAL;
+    if (dtype != CQIL_F32 && dtype != CQIL_BF16) return CQIL_EINVAL;
+    const int v = dtype == CQIL_BF16 ? 8 : 4;
+    if (L < 1 || L > 1024 || M < 1 || n < v || n % v) return CQIL_EINVAL;
+    if (!aligned16(X) || !aligned16(workspace)) return CQIL_EINVAL;
+    if (workspace_bytes < cqil_input_similarity_workspace_bytes(L, M)) return CQIL_ESIZE;
+    int chunks, per;
+    similarity_chunks(L, M, &chunks, &per);
+    return launch_similarity(X, dtype, L, M, n, sim, (float*)workspace, chunks, per, (hipStream_t)stream) == hipSuccess
+               ? CQIL_OK
+               : CQIL_EHIP;
+}
+
 int cqil_merge_lora(void* W, const void* A, const void* Bm, int dtype, int n_out, int n_in, int rank, float scale,
                     void* stream) {
     if (!W || !A || !Bm) return CQIL_EINVAL;

@@ -60,6 +60,9 @@ hipError_t launch_pack(const cqil_dims& d, int P, const PackArgs& src, char* pac
 hipError_t launch_merge_lora(void* W, const void* A, const void* Bm, int dtype, int n_out, int n_in, int r, float scale,
                              hipStream_t st);
 
+hipError_t launch_similarity(const void* X, int dtype, int L, int M, int n, float* sim, float* part, int chunks,
+                             int tokens_per_chunk, hipStream_t st);
+
 struct StepArgs {
     cqil_dims d;
     int P, bypass_d, B, T, advance;

@@ -181,4 +181,64 @@ hipError_t launch_merge_lora(void* W, const void* A, const void* Bm, int dtype, 
     return hipGetLastError();
 }
 
+// Similarity of layer inputs (Sec.3.1).  X [L][M][n]; a workgroup takes one pair (a, b <= a) and one chunk of
+// tokens, a wave one token at a time (16-byte loads, fp32 sums); the waves' cosines are added in wave order, the
+// chunks by the second kernel in chunk order: deterministic.  part [chunks][L][L].
+template <typename T>
+__global__ __launch_bounds__(256) void similarity_partial_kernel(const T* __restrict__ X, float* __restrict__ part,
+                                                                 int L, int M, int n, int tokens_per_chunk) {
+    constexpr int V = elem<T>::kVec;
+    __shared__ float wsum[4];
+    const int a = blockIdx.x, b = blockIdx.y, chunk = blockIdx.z;
+    if (b > a) return;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m0 = chunk * tokens_per_chunk, m1 = min(m0 + tokens_per_chunk, M);
+    float acc = 0.f;
+    for (int m = m0 + w; m < m1; m += 4) {
+        const T* xa = X + ((size_t)a * M + m) * n;
+        const T* xb = X + ((size_t)b * M + m) * n;
+        float dot = 0.f, na = 0.f, nb = 0.f;
+        for (int k = lane * V; k < n; k += 64 * V) {
+            float fa[V], fb[V];
+            elem<T>::unpack(load16(xa + k), fa);
+            elem<T>::unpack(load16(xb + k), fb);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                dot = fmaf(fa[e], fb[e], dot);
+                na = fmaf(fa[e], fa[e], na);
+                nb = fmaf(fb[e], fb[e], nb);
+            }
+        }
+        dot = wave_sum(dot); na = wave_sum(na); nb = wave_sum(nb);
+        if (na > 0.f && nb > 0.f) acc += dot / (sqrtf(na) * sqrtf(nb));
+    }
+    if (lane == 0) wsum[w] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) part[((size_t)chunk * L + a) * L + b] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+__global__ void similarity_reduce_kernel(const float* __restrict__ part, float* __restrict__ sim, int L, int M,
+                                         int chunks) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= L * L) return;
+    const int a = i / L, b = i % L;
+    const int hi = a > b ? a : b, lo = a > b ? b : a;  // only the lower triangle was computed
+    float s = 0.f;
+    for (int c = 0; c < chunks; ++c) s += part[((size_t)c * L + hi) * L + lo];
+    sim[i] = s / (float)M;
+}
+
+hipError_t launch_similarity(const void* X, int dtype, int L, int M, int n, float* sim, float* part, int chunks,
+                             int tokens_per_chunk, hipStream_t st) {
+    const dim3 grid(L, L, chunks);
+    if (dtype == CQIL_BF16)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(similarity_partial_kernel<bf16_t>), grid, dim3(256), 0, st, (const bf16_t*)X, part,
+                           L, M, n, tokens_per_chunk);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(similarity_partial_kernel<float>), grid, dim3(256), 0, st, (const float*)X, part,
+                           L, M, n, tokens_per_chunk);
+    hipLaunchKernelGGL(similarity_reduce_kernel, dim3((L * L + 255) / 256), dim3(256), 0, st, part, sim, L, M, chunks);
+    return hipGetLastError();
+}
+
 }  // namespace cqil

@@ -41,6 +41,18 @@ def test_merge_lora_validates_before_launching():
     assert L.cqil_merge_lora(0x1004, 0x1000, 0x1000, cq.CQIL_F32, 16, 32, 4, 1.0, None) == cq.CQIL_EINVAL  # alignment
 
 
+def test_input_similarity_validates_before_launching():
+    L = cq.lib()
+    need = L.cqil_input_similarity_workspace_bytes(6, 40)
+    assert need >= 6 * 6 * 4 and L.cqil_input_similarity_workspace_bytes(0, 40) == 0
+    args = (0x1000, cq.CQIL_BF16, 6, 40, 64, 0x1000, 0x1000)
+    assert L.cqil_input_similarity(None, *args[1:], need, None) == cq.CQIL_EINVAL
+    assert L.cqil_input_similarity(0x1000, 9, 6, 40, 64, 0x1000, 0x1000, need, None) == cq.CQIL_EINVAL
+    assert L.cqil_input_similarity(0x1000, cq.CQIL_BF16, 6, 40, 60, 0x1000, 0x1000, need, None) == cq.CQIL_EINVAL
+    assert L.cqil_input_similarity(0x1000, cq.CQIL_BF16, 2000, 40, 64, 0x1000, 0x1000, need, None) == cq.CQIL_EINVAL
+    assert L.cqil_input_similarity(*args, need - 1, None) == cq.CQIL_ESIZE
+
+
 def test_strerror_covers_all_codes():
     texts = {cq.strerror(c) for c in (0, -1, -2, -3, -4)}
     assert len(texts) == 5 and "unknown" not in " ".join(texts)

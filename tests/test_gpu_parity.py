@@ -106,6 +106,35 @@ def test_pack_group_is_a_bit_exact_index_map(shape, P, dtype):
         assert (raw[a:b] == 0xAB).all()
 
 
+# ------------------------------------------------------------------------------------------ Sec.3.1 tooling
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_input_similarity_of_captured_layer_inputs(dtype):
+    """Layer inputs captured from a chain of single-layer steps on the GPU (the inputs x_1..x_L and the final
+    state), compared with the oracle's similarity matrix of the same captured tensors; deterministic."""
+    L, T = 5, 37
+    pairs = [Pair(TINY, 1, dtype, max_seq=64, b_max=1, seed=600 + i, w_std=0.05, gain_jitter=0.1) for i in range(L)]
+    x = pairs[0].hidden(1, T, seed=5).cuda()
+    states = [x]
+    for p in pairs:
+        p.group.set_kv_len([0])
+        x = p.group.forward(x, 0, advance=False)
+        states.append(x)
+    X = torch.stack([s_[0] for s_ in states]).contiguous()          # [L+1, T, d_model]
+    sim = cq.cqil_input_similarity(X)
+    again = cq.cqil_input_similarity(X)
+    torch.cuda.synchronize()
+    assert torch.equal(sim, again)
+    ref = orc.input_similarity(synth.widen(X.cpu()))
+    got = sim.cpu().numpy()
+    say(f"  similarity {dtype}: adjacent layers {np.diag(ref, 1).round(4).tolist()}")
+    assert np.abs(got - ref).max() <= 1e-5                            # cosines are O(1); fp32 sums of the stored values
+    np.testing.assert_array_equal(got, got.T)
+    assert np.all(np.diag(ref, 1) < 0.99999), "the captured states are too alike to test anything"
+    # many tokens and a width that is not a multiple of a wave's stride: several chunks, ragged tail
+    Y = synth.normal((3, 1001, 200), 1.0, dtype, synth.generator(6)).cuda()
+    assert np.abs(cq.cqil_input_similarity(Y).cpu().numpy() - orc.input_similarity(synth.widen(Y.cpu()))).max() <= 1e-5
+
+
 # ------------------------------------------------------------------------------------------ LoRA merge
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_merge_lora_matches_oracle_and_feeds_the_group(dtype):
