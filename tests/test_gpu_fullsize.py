@@ -42,6 +42,16 @@ def test_config3_llama13b_group_P4_batch8_ragged():
     pair.step(pair.hidden(8, 1, seed=30), 1, label="cfg3")
 
 
+def test_wide_batch_llama13b_group_P4_batch40():
+    """A batch beyond the 32-row tile at full width (the batch sweep's regime): 40 sequences, ragged caches of
+    256..700 tokens, one new token each: 128-token tiles, K-split O and down projections, the four-wave attention."""
+    B = 40
+    lens = synth.kv_lengths(B, 256, 700, seed=1013)
+    pair = Pair(synth.SHAPES["13b"], 4, BF16, max_seq=704, b_max=B, seed=1013, gen_device="cuda")
+    pair.fill_cache(lens.tolist(), seed=2013, gen_device="cuda")
+    pair.step(pair.hidden(B, 1, seed=31), 1, label="13b batch 40")
+
+
 def test_config4_llama13b_prefill_P2_4x2048_sampled():
     """13B-shaped prefill, P=2, batch 4 x 2048 tokens, causal, empty caches, at full size on the GPU.
     The oracle computes the first 20 positions of two of the sequences (a causal prefix does not depend on
