@@ -551,21 +551,29 @@ __global__ __launch_bounds__(kThreads) void head_kernel(const T* __restrict__ hi
     }
 }
 
-// greedy token: lowest index among the maxima.  One workgroup per sequence.
-__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int32_t* __restrict__ next, int vocab) {
-    __shared__ float bv[256];
-    __shared__ int bi[256];
+// greedy token: lowest index among the maxima.  One workgroup of 1024 threads per sequence; 16-byte loads when the
+// rows allow it.
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int32_t* __restrict__ next, int vocab) {
+    __shared__ float bv[1024];
+    __shared__ int bi[1024];
     const int b = blockIdx.x, tid = threadIdx.x;
     const float* lg = logits + (size_t)b * vocab;
     float best = -INFINITY;
     int idx = 0x7fffffff;
-    for (int v = tid; v < vocab; v += 256) {
-        const float x = lg[v];
+    auto take = [&](float x, int v) {
         if (x > best || (x == best && v < idx)) { best = x; idx = v; }
+    };
+    if ((vocab & 3) == 0 && (((uintptr_t)logits) & 15) == 0) {
+        for (int v = 4 * tid; v < vocab; v += 4096) {
+            const float4 x = *reinterpret_cast<const float4*>(lg + v);
+            take(x.x, v); take(x.y, v + 1); take(x.z, v + 2); take(x.w, v + 3);
+        }
+    } else {
+        for (int v = tid; v < vocab; v += 1024) take(lg[v], v);
     }
     bv[tid] = best; bi[tid] = idx;
     __syncthreads();
-    for (int s = 128; s >= 1; s >>= 1) {
+    for (int s = 512; s >= 1; s >>= 1) {
         if (tid < s) {
             const float ov = bv[tid + s];
             const int oi = bi[tid + s];
@@ -588,7 +596,7 @@ hipError_t launch_head(const HeadArgs& h, hipStream_t st) {
         hipLaunchKernelGGL(HIP_KERNEL_NAME(head_kernel<float>), grid, dim3(kThreads), (xw + 16) * sizeof(float), st,
                            (const float*)h.hidden, (const float*)h.g_final, (const float*)h.lm_head, h.logits, h.T,
                            h.d.d_model, h.vocab, rows, h.d.rms_eps);
-    if (h.next_token) hipLaunchKernelGGL(argmax_kernel, dim3(h.B), dim3(256), 0, st, h.logits, h.next_token, h.vocab);
+    if (h.next_token) hipLaunchKernelGGL(argmax_kernel, dim3(h.B), dim3(1024), 0, st, h.logits, h.next_token, h.vocab);
     return hipGetLastError();
 }
 

@@ -456,6 +456,32 @@ def test_model_forward_general_partitions(L, p, s, e):
         tokens = torch.from_numpy(ref["next"].reshape(1, 1).astype(np.int32))
 
 
+@pytest.mark.parametrize("vocab", [1003, 1024])
+def test_greedy_token_is_the_lowest_index_among_equal_maxima(vocab):
+    """Ties in the logits (duplicated and all-zero rows of the lm head): the greedy token is the first maximum."""
+    dtype, max_seq = torch.float32, 16
+    model, groups, kv_len, nl, emb, gfin, head = _tiny_model(dtype, [1, 2], vocab, max_seq, seed=910)
+    lm = model._keep[6]
+    lm.zero_()
+    v = synth.normal((TINY.d_model,), 1.0, dtype, synth.generator(3)).cuda()
+    for row in (977, 41, 500, 42):
+        lm[row] = v
+    tokens = torch.randint(0, vocab, (1, 4), generator=synth.generator(2)).to(torch.int32).cuda()
+    ws = torch.empty(cq.cqil_model_workspace_bytes(model, 1, 4), dtype=torch.uint8, device="cuda")
+    logits = torch.empty(1, vocab, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+    for sign in (1.0, -1.0):
+        for row in (977, 41, 500, 42):
+            lm[row] = sign * v
+        kv_len.zero_(); model.c.max_kv_len = 0
+        cq.cqil_model_forward(model, tokens, 1, 4, 1, False, None, logits, nxt, ws)
+        torch.cuda.synchronize()
+        lg = logits.cpu().numpy()[0]
+        assert (lg[[41, 42, 500, 977]] == lg[41]).all() and lg[0] == 0.0
+        assert nxt.item() == int(np.argmax(lg))              # numpy returns the first maximum: 41 or 0
+        assert nxt.item() in (0, 41)
+
+
 def test_model_forward_equals_chain_of_group_calls():
     """Bit-for-bit: the model loop is the embedding followed by cqil_group_forward per group."""
     dtype, vocab, max_seq = torch.bfloat16, 257, 32
