@@ -13,8 +13,8 @@
 // its column (two cross-lane steps), the running maximum / sum / output are rescaled per key tile (online softmax).
 //
 // Workgroup: 4 waves, 128 queries (32 per wave: two column tiles), key tiles of 64.  K tile and V^T tile are
-// staged in LDS as 1 KiB tiles in A-operand order; the next tile's K and V rows are fetched into registers while
-// the current one is multiplied.  V is transposed in registers: a thread fetches 4 values of d for the 8 keys of
+// staged in LDS as 1 KiB tiles in A-operand order, in two stages: while a tile is multiplied the next one goes
+// from registers to the other stage and the one after that is fetched (one barrier per tile).  V is transposed in registers: a thread fetches 4 values of d for the 8 keys of
 // one operand piece and writes 4 complete 16-byte pieces (no sub-word LDS writes).
 #pragma once
 #include "cqil_dev.h"
@@ -43,8 +43,9 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
     constexpr int NVG = (kPfBKV / 8) * (DK / 4);            // V groups (8 keys x 4 d) of a tile
     constexpr int VG = (NVG + kPfThreads - 1) / kPfThreads;  // per thread (the last round may be partial: whole waves)
     static_assert(KPT >= 1 && NVG % 64 == 0, "tile too small for the workgroup");
-    __shared__ __align__(16) bf16_t Ks[4 * NDB * TE];   // [key tile 0..3][d block]
-    __shared__ __align__(16) bf16_t Vs[NDT * 2 * TE];   // [d tile][key block 0..1]
+    constexpr int KSZ = 4 * NDB * TE, VSZ = NDT * 2 * TE;
+    __shared__ __align__(16) bf16_t Ks2[2 * KSZ];   // two stages of [key tile 0..3][d block]
+    __shared__ __align__(16) bf16_t Vs2[2 * VSZ];   // two stages of [d tile][key block 0..1]
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int j = lane & 15, g = lane >> 4;
@@ -81,14 +82,14 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
     // ---- staging roles.  K: piece p = tid + 256 q -> key p / PPK, piece c = p % PPK of the row.
     // V: group v = tid + 256 q -> d quad dq = v % (DK/4), key group kgp = v / (DK/4): the 8 keys of operand piece
     // (kb2 = kgp >> 2, g = kgp & 3), i.e. key 32 kb2 + 16 (e >> 2) + 4 g + (e & 3) for slot e.
-    uint4 kreg[KPT];
+    u32x4 kreg[KPT];  // vector type, not the uint4 struct: struct copies through memcpy kept this array in memory
     uint2 vreg[VG][8];
-    auto fetch = [&](int key0) {
+    auto fetch = [&](int key0) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < KPT; ++q) {
             const int p = tid + kPfThreads * q;
             const int slot = min(key0 + p / PPK, kv_end - 1);  // rows past the end: any row, they are masked
-            kreg[q] = *reinterpret_cast<const uint4*>(kg + (size_t)slot * DK + 8 * (p % PPK));
+            kreg[q] = *reinterpret_cast<const u32x4*>(kg + (size_t)slot * DK + 8 * (p % PPK));
         }
 #pragma unroll
         for (int q = 0; q < VG; ++q) {
@@ -100,18 +101,22 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
                 const int key = 32 * (kgp >> 2) + 16 * (e >> 2) + 4 * (kgp & 3) + (e & 3);
                 const int slot = key0 + key;
                 // V rows past the end must be zero: their probabilities are zero, but 0 * garbage may be NaN
-                vreg[q][e] = (slot < kv_end) ? *reinterpret_cast<const uint2*>(vg + (size_t)slot * DK + 4 * dq) : make_uint2(0, 0);
+                const uint2 raw = *reinterpret_cast<const uint2*>(vg + (size_t)min(slot, kv_end - 1) * DK + 4 * dq);
+                const uint32_t keep = slot < kv_end ? 0xffffffffu : 0u;
+                vreg[q][e] = make_uint2(raw.x & keep, raw.y & keep);
             }
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+        bf16_t* Ks = Ks2 + buf * KSZ;
+        bf16_t* Vs = Vs2 + buf * VSZ;
 #pragma unroll
         for (int q = 0; q < KPT; ++q) {
             const int p = tid + kPfThreads * q;
             const int key = p / PPK, c = p % PPK;
             const int kt = key >> 4, i = key & 15, db = c >> 2, gg = c & 3;
             const int pos = gg * 16 + ((i + 4 * gg + 2 * (db & 1) + (db >> 1)) & 15);
-            *reinterpret_cast<uint4*>(Ks + (kt * NDB + db) * TE + pos * 8) = kreg[q];
+            *reinterpret_cast<u32x4*>(Ks + (kt * NDB + db) * TE + pos * 8) = kreg[q];
         }
 #pragma unroll
         for (int q = 0; q < VG; ++q) {
@@ -151,12 +156,15 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
     float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
     const float scale2 = 1.4426950408889634f / sqrtf((float)DK);  // scores in units of log 2: exp(x) = exp2(x log2 e)
 
+    // Two LDS stages: while a tile is multiplied, the next one (already in registers) is written to the other
+    // stage and the one after that is fetched; one barrier per tile.
     fetch(0);
-    for (int key0 = 0; key0 < kv_end; key0 += kPfBKV) {
-        __syncthreads();  // the previous tile has been consumed
-        stage();
-        __syncthreads();
-        if (key0 + kPfBKV < kv_end) fetch(key0 + kPfBKV);  // in flight during the products below
+    stage(0);
+    fetch(kPfBKV);  // unconditional: rows past the end are clamped (K) or zero (V)
+    __syncthreads();
+    for (int key0 = 0, it_tile = 0; key0 < kv_end; key0 += kPfBKV, ++it_tile) {
+        const bf16_t* Ks = Ks2 + (it_tile & 1) * KSZ;
+        const bf16_t* Vs = Vs2 + (it_tile & 1) * VSZ;
 
         // ---- S^T = K Q^T for 4 key tiles x 2 query tiles
         attn_f32x4 s[4][2];
@@ -174,6 +182,9 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
                                                                         __builtin_bit_cast(attn_bf16x8, qf[jt][ks]), s[it][jt], 0, 0, 0);
             }
         }
+        // the other stage was last read before the previous barrier: write the next tile there, fetch the one after
+        stage((it_tile & 1) ^ 1);       // after the last tile: a tile of clamped rows that nobody reads
+        fetch(key0 + 2 * kPfBKV);
         // ---- mask, online softmax (per query = per column), P fragments
         uint4 pk[2][2];  // [key block][query tile]
 #pragma unroll
@@ -228,6 +239,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
                     acc[dt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(attn_bf16x8, vf),
                                                                           __builtin_bit_cast(attn_bf16x8, pk[kb2][jt]), acc[dt][jt], 0, 0, 0);
             }
+        __syncthreads();  // this stage is free again, the next one is complete
     }
 
     // ---- normalise and store: lane (j, g) holds d = 16 dt + 4 g .. + 3 of query j
