@@ -27,6 +27,11 @@ namespace cqil {
 
 typedef __bf16 gemm_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float gemm_f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t gemm_u32x4 __attribute__((ext_vector_type(4)));
+
+// buffer descriptors of the operand loads: raw buffers (stride 0) of 2 GiB from a wave-uniform base; the launcher
+// checks that no offset reaches that range.  Word 3: 32-bit data format, no swizzle (the gfx9 / CDNA encoding).
+constexpr uint32_t kGemmBufRange = 0x80000000u, kGemmBufFlags = 0x00020000u;
 
 // epilogues: plain store, + fp32 residual R[m][n], or SwiGLU over block-interleaved gate / up rows
 constexpr int kEpiNone = 0, kEpiAddR = 1, kEpiSwiglu = 2;
@@ -81,46 +86,56 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     // piece (2 hf + gg) * 16 + (i & 15) of tile kt for the 16-column slab k16 = 2 kt + hf: 256 elements per slab
     const int fi = lane & 31, fgg = lane >> 5;
     const int n_k16 = 2 * n_ktiles;
-    const bf16_t* wp[2];
+    // Both operands come by buffer loads (wave-uniform base in scalar registers + a per-lane byte offset fixed for
+    // the whole product + a wave-uniform offset per slab / step): no per-lane address arithmetic in the loop.
+    const bf16_t* wbase = W + (((size_t)z * strip_step + n0 / 16) * w_tiles_per_strip + (size_t)z * ktile_step) * TE;
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(wbase), 0, kGemmBufRange, kGemmBufFlags);
+    uint32_t wvo[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-        const int strip = min(n0 / 16 + 4 * wn + 2 * s + (fi >> 4), n_strips - 1);
-        wp[s] = W + (((size_t)z * strip_step + strip) * w_tiles_per_strip + (size_t)z * ktile_step) * TE +
-                (fgg * 16 + (fi & 15)) * 8;
+        const int rel = min(4 * wn + 2 * s + (fi >> 4), n_strips - 1 - n0 / 16);
+        wvo[s] = (uint32_t)(((size_t)rel * w_tiles_per_strip * TE + (fgg * 16 + (fi & 15)) * 8) * 2);
     }
-    uint4 wf[4][2];  // [slab of the step][s]
+    gemm_u32x4 wf[4][2];  // [slab of the step][s]
     auto load_w = [&](int b, int k16) {
-        const size_t off = (size_t)min(k16, n_k16 - 1) * 256;
+        const uint32_t soff = (uint32_t)min(k16, n_k16 - 1) * 512u;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) wf[b][s] = *reinterpret_cast<const uint4*>(wp[s] + off);
+        for (int s = 0; s < 2; ++s) wf[b][s] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wvo[s], soff, 0);
     };
 
     // activation pieces: thread -> (row, 16-byte piece c) of the 64-column step, APT rows NT/8 apart
     const int c = tid & 7;
-    const bf16_t* ap[APT];
+    const __amdgpu_buffer_rsrc_t arsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A + (size_t)m0 * lda), 0, kGemmBufRange, kGemmBufFlags);
+    uint32_t avo[APT];
     int a_lds[APT];
 #pragma unroll
     for (int q = 0; q < APT; ++q) {
         const int row = (tid >> 3) + (NT / 8) * q;
-        ap[q] = A + (size_t)min(m0 + row, M - 1) * lda;
+        avo[q] = (uint32_t)(((size_t)min(row, M - 1 - m0) * lda + 8 * c) * 2);
         const int ts = row >> 5, j = row & 31, k16 = c >> 1, gg = c & 1;
         a_lds[q] = (ts * 4 + k16) * TE + (gg * 32 + ((j + c) & 31)) * 8;
     }
-    uint4 areg[APT];
+    // In the last step a piece may lie past column K: it is read from columns K - 8 .. K - 1 instead (a_tail < 0
+    // moves the lane there) and replaced by zeros when it goes to LDS.  Steps past the last read the last again.
+    const int last_step = n_steps - 1;
+    const int a_tail = (64 * last_step + 8 * c < K) ? 0 : 2 * (K - 8 - 64 * last_step - 8 * c);
+    gemm_u32x4 areg[APT];
     uint32_t a_keep = 0;  // all ones if the loaded columns exist, else zero (applied when the pieces go to LDS)
     auto load_a = [&](int step) {
-        const int k = 64 * step + 8 * c;
-        const bool ok = k < K;
-        const int kc = ok ? k : K - 8;
-        a_keep = ok ? 0xffffffffu : 0u;
+        a_keep = (64 * step + 8 * c < K) ? 0xffffffffu : 0u;
+        const uint32_t soff = (uint32_t)min(step, last_step) * 128u;
+        const int adj = step >= last_step ? a_tail : 0;
 #pragma unroll
-        for (int q = 0; q < APT; ++q) areg[q] = *reinterpret_cast<const uint4*>(ap[q] + kc);
+        for (int q = 0; q < APT; ++q)
+            areg[q] = __builtin_amdgcn_raw_buffer_load_b128(arsrc, avo[q] + (uint32_t)adj, soff, 0);
     };
     auto store_a = [&](bf16_t* as) {
 #pragma unroll
         for (int q = 0; q < APT; ++q)
             *reinterpret_cast<uint4*>(as + a_lds[q]) =
-                make_uint4(areg[q].x & a_keep, areg[q].y & a_keep, areg[q].z & a_keep, areg[q].w & a_keep);
+                make_uint4(areg[q][0] & a_keep, areg[q][1] & a_keep, areg[q][2] & a_keep, areg[q][3] & a_keep);
     };
 
     gemm_f32x16 acc[TT][2];
@@ -148,11 +163,12 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
                                                                     __builtin_bit_cast(gemm_bf16x8, af[t]), acc[t][s], 0, 0, 0);
     };
 
-    // Software pipeline, one slab (16 columns, 8 instructions) per stage: the fragments of slab b+1 are read
-    // from LDS before the instructions of slab b are issued, the weights of a slab are fetched a whole step ahead,
-    // and the next step's activations are written to the other LDS stage before the third slab's instructions, so
-    // that the single barrier of a step is passed while those are in the pipe.  The scheduling barriers keep the
-    // compiler from undoing the order.
+    // Software pipeline, one slab (16 columns, 2 TT instructions) per stage: the fragments of slab b+1 are read
+    // from LDS while the instructions of slab b issue, the weights of a slab are fetched a whole step ahead, the
+    // activations two steps ahead, and the next step's activations are written to the other LDS stage during the
+    // third slab, so that the single barrier of a step is passed while those are in the pipe.  Within a stage the
+    // scheduling groups spread the memory instructions one by one between the matrix instructions (issued in a
+    // burst they cost about 8 % of the throughput); the scheduling barriers keep the stages apart.
     uint4 afa[TT], afb[TT];
     const int steps_per_slice = (n_steps + ksplit - 1) / ksplit;
     const int s_beg = ks * steps_per_slice, s_end = min(s_beg + steps_per_slice, n_steps);  // may be empty
@@ -160,33 +176,67 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
 #pragma unroll
     for (int b = 0; b < 4; ++b) load_w(b, 4 * s_beg + b);
     store_a(lds);
+    load_a(s_beg + 1);
     __syncthreads();
     read_af(afa, lds, 0);
+    constexpr int kMfma = 0x008, kVmemRd = 0x020, kDsRd = 0x100, kDsWr = 0x200;  // scheduling group masks
     for (int step = s_beg; step < s_end; ++step) {
         bf16_t* cur = lds + ((step - s_beg) & 1) * STAGE;
         bf16_t* nxt = lds + (((step - s_beg) & 1) ^ 1) * STAGE;
         const int k16n = 4 * (step + 1);
-        load_a(step + 1);  // beyond the last step: zeros, stored to the idle stage and never used
         read_af(afb, cur, 1);
-        __builtin_amdgcn_sched_barrier(0);
         mma(afa, 0);
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            __builtin_amdgcn_sched_group_barrier(kDsRd, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(kMfma, 2, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
         load_w(0, k16n);
         read_af(afa, cur, 2);
-        __builtin_amdgcn_sched_barrier(0);
         mma(afb, 1);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            __builtin_amdgcn_sched_group_barrier(kVmemRd, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        }
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            __builtin_amdgcn_sched_group_barrier(kDsRd, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
         load_w(1, k16n + 1);
         read_af(afb, cur, 3);
-        store_a(nxt);
-        __builtin_amdgcn_sched_barrier(0);
+        store_a(nxt);  // beyond the last step: zeros, stored to the idle stage and never used
+        load_a(step + 2);
         mma(afa, 2);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            __builtin_amdgcn_sched_group_barrier(kVmemRd, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        }
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            __builtin_amdgcn_sched_group_barrier(kDsRd, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < APT; ++q) {
+            __builtin_amdgcn_sched_group_barrier(kDsWr, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(kVmemRd, 1, 0);
+            if (q < TT - 2) __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
         load_w(2, k16n + 2);
         __syncthreads();
         read_af(afa, nxt, 0);
-        __builtin_amdgcn_sched_barrier(0);
         mma(afb, 3);
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            __builtin_amdgcn_sched_group_barrier(kDsRd, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(kMfma, 2, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
         load_w(3, k16n + 3);
     }
@@ -316,6 +366,7 @@ static hipError_t gemm_mfma(int tile_sel, const bf16_t* A, const bf16_t* W, CT* 
                             size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step,
                             size_t sC, hipStream_t st, float* part = nullptr, size_t part_floats = 0) {
     if (M < 1 || (N & 3) || (K & 7) || K < 8) return hipErrorInvalidValue;
+    if (Kp >= (1u << 21) || lda >= (1u << 21)) return hipErrorInvalidValue;  // byte offsets of a tile stay below 2 GiB
     // default: 128 x 256 (two workgroups per CU overlap each other's barriers and load latency)
     // up to 32 token rows (a batch of decode rows): one 32-token tile per wave, a quarter of the matrix-core and LDS
     // work per weight byte streamed
