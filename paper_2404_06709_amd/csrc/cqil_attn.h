@@ -60,12 +60,12 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
         for (int u = 0; u < U; ++u) {
             const int s = (i0 + u) * SPW + sg;
             ok[u] = s < S;
-            kraw[u] = ok[u] ? load16(kb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
+            kraw[u] = ok[u] ? load16_stream(kb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int s = (i0 + u) * SPW + sg;
-            vraw[u] = ok[u] ? load16(vb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
+            vraw[u] = ok[u] ? load16_stream(vb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
         }
         float sc[U], mloc = -INFINITY;
 #pragma unroll

@@ -97,11 +97,13 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
         const int rel = min(4 * wn + 2 * s + (fi >> 4), n_strips - 1 - n0 / 16);
         wvo[s] = (uint32_t)(((size_t)rel * w_tiles_per_strip * TE + (fgg * 16 + (fi & 15)) * 8) * 2);
     }
+    // a single band of token tiles (TT == 1: up to 32 tokens) reads every weight once: streaming (non-temporal) loads
+    constexpr int kWeightAux = TT == 1 ? 2 : 0;
     gemm_u32x4 wf[4][2];  // [slab of the step][s]
     auto load_w = [&](int b, int k16) {
         const uint32_t soff = (uint32_t)min(k16, n_k16 - 1) * 512u;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) wf[b][s] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wvo[s], soff, 0);
+        for (int s = 0; s < 2; ++s) wf[b][s] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wvo[s], soff, kWeightAux);
     };
 
     // activation pieces: thread -> (row, 16-byte piece c) of the 64-column step, APT rows NT/8 apart
