@@ -49,7 +49,7 @@ __device__ __forceinline__ void gemm_store4(float* p, const float (&v)[4]) {
 // N, K: logical sizes of this group's product; N % 4 == 0, K % 8 == 0, M >= 1.  strip_step / ktile_step: group
 // strides in 16-row strips / 32-column tiles inside W.  R (kEpiAddR): fp32 [M][N] added to the result.
 // kEpiSwiglu: N % 32 == 0 rows as blocks of 16 gate + 16 up rows; C gets N / 2 columns per group.
-template <typename CT, int EPI, int WM, int WN, int TT>
+template <typename CT, int EPI, int WM, int WN, int TT, bool WSTREAM>
 __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, CT* __restrict__ C, const float* __restrict__ R, int M,
     int N, int K, size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t strip_step, size_t ktile_step,
@@ -97,8 +97,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
         const int rel = min(4 * wn + 2 * s + (fi >> 4), n_strips - 1 - n0 / 16);
         wvo[s] = (uint32_t)(((size_t)rel * w_tiles_per_strip * TE + (fgg * 16 + (fi & 15)) * 8) * 2);
     }
-    // a single band of token tiles (TT == 1: up to 32 tokens) reads every weight once: streaming (non-temporal) loads
-    constexpr int kWeightAux = TT == 1 ? 2 : 0;
+    // WSTREAM: a single band of token tiles reads every weight once: streaming (non-temporal) loads
+    constexpr int kWeightAux = WSTREAM ? 2 : 0;
     gemm_u32x4 wf[4][2];  // [slab of the step][s]
     auto load_w = [&](int b, int k16) {
         const uint32_t soff = (uint32_t)min(k16, n_k16 - 1) * 512u;
@@ -350,9 +350,14 @@ static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, cons
     const long supers = (long)groups * ksplit * ((nx + SN - 1) / SN) * ((ny + SM - 1) / SM);
     const long wgs = (supers + 7) / 8 * 8 * SM * SN;
     if (wgs > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, EPI, WM, WN, TT>), dim3((unsigned)wgs), dim3(64 * WM * WN),
-                       lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16, k_step / 32, sC, ksplit,
-                       part);
+    if (ny == 1)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, EPI, WM, WN, TT, true>), dim3((unsigned)wgs),
+                           dim3(64 * WM * WN), lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16,
+                           k_step / 32, sC, ksplit, part);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, EPI, WM, WN, TT, false>), dim3((unsigned)wgs),
+                           dim3(64 * WM * WN), lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16,
+                           k_step / 32, sC, ksplit, part);
     if (ksplit > 1) {
         const size_t total = (size_t)groups * M * N / 4;
         const unsigned g = (unsigned)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
