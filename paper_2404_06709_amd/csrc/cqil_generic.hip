@@ -261,6 +261,77 @@ __global__ __launch_bounds__(1024) void bypass_norm_kernel(const T* __restrict__
     }
 }
 
+// The same for rows of at most 1024 16-byte chunks and groups of at most 8 layers: a thread owns one chunk, reads x
+// and the P attention outputs of it once and keeps them in registers, so the row crosses the memory system once
+// (the general kernel re-reads the window in every pass).  blockDim.x >= d_model / V, a multiple of 64.
+constexpr int kBypassRegLayers = 8;
+template <typename T>
+__global__ __launch_bounds__(1024) void bypass_norm_reg_kernel(const T* __restrict__ x, const float* __restrict__ a,
+                                                              const T* __restrict__ g_ffn, T* __restrict__ nrm,
+                                                              float* __restrict__ resid, int P, int bypass_d, int M,
+                                                              int d_model, float eps, int32_t* __restrict__ kv_len,
+                                                              int advance_B, int advance_T) {
+    constexpr int V = elem<T>::kVec;
+    __shared__ float scratch[16];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const bool act = tid < d_model / V;
+    const int k = act ? tid * V : 0;
+    float xv[V], av[kBypassRegLayers][V];
+    elem<T>::unpack(load16(x + (size_t)m * d_model + k), xv);
+#pragma unroll
+    for (int j = 0; j < kBypassRegLayers; ++j) {
+        if (j < P) {
+            const float* ap = a + ((size_t)j * M + m) * d_model + k;
+#pragma unroll
+            for (int e = 0; e < V; e += 4) {
+                const float4 t = *reinterpret_cast<const float4*>(ap + e);
+                av[j][e] = t.x; av[j][e + 1] = t.y; av[j][e + 2] = t.z; av[j][e + 3] = t.w;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) av[j][e] = 0.f;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kBypassRegLayers; ++i) {
+        if (i >= P) break;
+        const int jlo = bypass_d < 0 ? i + 1 : max(0, i - bypass_d);  // negative: Eq.5, the input is x alone
+        float hv[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) hv[e] = xv[e];
+#pragma unroll
+        for (int j = 0; j <= i; ++j) {
+            if (j >= jlo) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) hv[e] += av[j][e];
+            }
+        }
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < V; ++e) ss += hv[e] * hv[e];
+        ss = block_sum(act ? ss : 0.f, scratch);
+        const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
+        if (act) {
+            float gv[V];
+            elem<T>::unpack(load16(g_ffn + (size_t)i * d_model + k), gv);
+#pragma unroll
+            for (int e = 0; e < V; ++e) hv[e] = hv[e] * r * gv[e];
+            *reinterpret_cast<uint4*>(nrm + ((size_t)i * M + m) * d_model + k) = pack16(hv, (const T*)nullptr);
+        }
+    }
+    if (advance_B > 0 && m == 0)
+        for (int b = tid; b < advance_B; b += blockDim.x) kv_len[b] += advance_T;
+    if (act) {
+#pragma unroll
+        for (int j = 0; j < kBypassRegLayers; ++j)
+#pragma unroll
+            for (int e = 0; e < V; ++e) xv[e] += av[j][e];  // layers past P hold zeros
+#pragma unroll
+        for (int e = 0; e < V; e += 4)
+            *reinterpret_cast<float4*>(resid + (size_t)m * d_model + k + e) = make_float4(xv[e], xv[e + 1], xv[e + 2], xv[e + 3]);
+    }
+}
+
 // u[m][l*f + j] = silu(gate) * up, reading the block-interleaved gate/up columns
 template <typename T>
 __global__ void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ u, int P, int M, int d_ffn) {
@@ -462,8 +533,12 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     }
     if ((ge = gemm_any<T, float, false>(ctx, wo, a, nullptr, M, dm, dm, dm, (size_t)P * dm, dm, P, Mdm, 0, (size_t)dm, Mdm, st,
                                         part, s.wl.gemm_part_floats)) != hipSuccess) return ge;
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(row_threads), 0, st, x, a, g_ffn, nrm, resid,
-                       P, bd, M, dm, d.rms_eps, s.kv_len, s.advance ? s.B : 0, s.T);
+    if (P <= kBypassRegLayers && dm / elem<T>::kVec <= 1024)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_reg_kernel<T>), dim3(M), dim3((dm / elem<T>::kVec + 63) / 64 * 64), 0,
+                           st, x, a, g_ffn, nrm, resid, P, bd, M, dm, d.rms_eps, s.kv_len, s.advance ? s.B : 0, s.T);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(row_threads), 0, st, x, a, g_ffn, nrm,
+                           resid, P, bd, M, dm, d.rms_eps, s.kv_len, s.advance ? s.B : 0, s.T);
     if constexpr (std::is_same<T, bf16_t>::value) {
         // gate/up product with SwiGLU in the epilogue: u is written directly, gate and up never reach memory
         if ((ge = gemm_mfma<bf16_t, kEpiSwiglu>(g_tune.gemm_tile, nrm, wgu, u, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * f,

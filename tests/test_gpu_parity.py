@@ -216,6 +216,18 @@ def test_every_bypass_distance_decode_and_prefill(P, dtype):
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_group_wider_than_eight_layers(dtype):
+    """Ten layers in one group: beyond the eight whose attention outputs the bypass kernel keeps in registers, so
+    the general kernel of the token-parallel path (and the decode kernels at P = 10) are the ones checked."""
+    P = 10
+    pair = Pair(TINY, P, dtype, max_seq=96, b_max=2, seed=2100, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([20, 5], seed=13)
+    for d in (0, 3, P - 1):
+        pair.step(pair.hidden(1, 1, seed=50 + d), d, label=f"P={P} d={d} decode {dtype}")
+        pair.step(pair.hidden(2, 3, seed=60 + d), d, label=f"P={P} d={d} prefill {dtype}")
+
+
 def test_decode_is_deterministic_and_in_place():
     pair = Pair(TINY, 4, torch.float32, max_seq=300, b_max=1, seed=5, w_std=0.05, gain_jitter=0.1)
     pair.fill_cache([260], seed=9)
