@@ -506,7 +506,9 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
     if constexpr (std::is_same<T, bf16_t>::value) {
         // matrix-core attention for the head sizes it is built for; positions were bounded by the caller
         if (!attn_done && (dk == 64 || dk == 128)) {
-            const dim3 grid((s.T + kPfBQ - 1) / kPfBQ, P * s.B * nh);
+            // 1-D grid: 8 XCDs x groups of kPfUnitGroup head units x query blocks (the kernel skips the padding)
+            const int nqb = (s.T + kPfBQ - 1) / kPfBQ, units_per_xcd = (P * s.B * nh + 7) / 8;
+            const dim3 grid(8u * ((units_per_xcd + kPfUnitGroup - 1) / kPfUnitGroup) * kPfUnitGroup * nqb);
             if (dk == 64)
                 hipLaunchKernelGGL(HIP_KERNEL_NAME(attn_prefill_mfma_kernel<64>), grid, dim3(kPfThreads), 0, st,
                                    (const bf16_t*)qkv, (const bf16_t*)s.kc, (const bf16_t*)s.vc, s.kv_len, ctx, P, s.B, s.T,

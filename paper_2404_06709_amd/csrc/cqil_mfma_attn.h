@@ -25,6 +25,7 @@ typedef __bf16 attn_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float attn_f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPfBQ = 128, kPfBKV = 64, kPfThreads = 256;
+constexpr int kPfUnitGroup = 8;  // head units whose query blocks are interleaved on one XCD
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return f32x2_to_bf16x2(a, b);
@@ -49,9 +50,20 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int j = lane & 15, g = lane >> 4;
-    const int qb = gridDim.x - 1 - blockIdx.x;  // long (late) query blocks first
-    const int h = blockIdx.y % n_heads;
-    const int lb = blockIdx.y / n_heads;
+    // Workgroup -> (head unit, query block).  The hardware deals consecutive workgroups of the 1-D grid to the 8
+    // XCDs in turn, and each XCD has its own L2: unit u = (layer, sequence, head) is given to XCD u mod 8, so its keys
+    // and values are fetched into one L2 only and all its query blocks find them there.  On an XCD, units are taken
+    // kPfUnitGroup at a time and their query blocks longest (latest) first: the 64 workgroups an XCD runs at once
+    // are then a mix of long and short blocks of a few units.  (With a 2-D grid of query block x unit every XCD read
+    // every unit: 1.12 ms against 0.70 ms at 13B, P=2, B=4, T=2048.)
+    const int nqb = (T_new + kPfBQ - 1) / kPfBQ, units = P * B * n_heads;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int grp = slot / (kPfUnitGroup * nqb), i_in = slot % (kPfUnitGroup * nqb);
+    const int qb = nqb - 1 - i_in / kPfUnitGroup;
+    const int unit = xcd + 8 * (grp * kPfUnitGroup + i_in % kPfUnitGroup);
+    if (unit >= units) return;  // padding of the grid (whole workgroup)
+    const int h = unit % n_heads;
+    const int lb = unit / n_heads;
     const int b = lb % B, l = lb / B;
     const int M = B * T_new;
     const size_t d_model = (size_t)n_heads * DK;
