@@ -160,6 +160,12 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
         }
     };
 
+    // first query position of the wave (queries past T_new are not stored: they go unmasked and do not count)
+    int qmin = min(qpos[0] < 0 ? 0x7fffffff : qpos[0], qpos[1] < 0 ? 0x7fffffff : qpos[1]);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) qmin = min(qmin, __shfl_xor(qmin, off, kWave));
+    qmin = __builtin_amdgcn_readfirstlane(qmin);
+
     attn_f32x4 acc[NDT][2];
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt)
@@ -199,31 +205,41 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
         fetch(key0 + 2 * kPfBKV);
         // ---- mask, online softmax (per query = per column), P fragments
         uint4 pk[2][2];  // [key block][query tile]
+        // only tiles that reach past the wave's first query need the causal mask (wave-uniform)
+        const bool masked = key0 + kPfBKV - 1 > qmin;
 #pragma unroll
         for (int jt = 0; jt < 2; ++jt) {
+            // running maximum in raw score units; the scale (log2 e / sqrt(d_k) > 0) enters in the exponent's fma
             float mloc = -INFINITY;
+            if (masked) {
 #pragma unroll
-            for (int it = 0; it < 4; ++it)
+                for (int it = 0; it < 4; ++it)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = key0 + 16 * it + 4 * g + r;
-                    const float v = (key <= qpos[jt]) ? s[it][jt][r] * scale2 : -INFINITY;
-                    s[it][jt][r] = v;
-                    mloc = fmaxf(mloc, v);
-                }
+                    for (int r = 0; r < 4; ++r) {
+                        const int key = key0 + 16 * it + 4 * g + r;
+                        const float v = (key <= qpos[jt]) ? s[it][jt][r] : -INFINITY;
+                        s[it][jt][r] = v;
+                        mloc = fmaxf(mloc, v);
+                    }
+            } else {
+#pragma unroll
+                for (int it = 0; it < 4; ++it)
+                    mloc = fmaxf(fmaxf(mloc, fmaxf(s[it][jt][0], s[it][jt][1])), fmaxf(s[it][jt][2], s[it][jt][3]));
+            }
             mloc = fmaxf(mloc, __shfl_xor(mloc, 16, kWave));
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
             const float mnew = fmaxf(mrun[jt], mloc);
             // exp2(-inf) = 0 covers the first tile and masked keys; a query with no key yet keeps mnew = -inf
             const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-            const float corr = __builtin_amdgcn_exp2f(mrun[jt] - msafe);
+            const float corr = __builtin_amdgcn_exp2f((mrun[jt] - msafe) * scale2);
+            const float moff = -msafe * scale2;
             float psum = 0.f;
             float p[4][4];
 #pragma unroll
             for (int it = 0; it < 4; ++it)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    p[it][r] = __builtin_amdgcn_exp2f(s[it][jt][r] - msafe);
+                    p[it][r] = __builtin_amdgcn_exp2f(fmaf(s[it][jt][r], scale2, moff));
                     psum += p[it][r];
                 }
             lrun[jt] = lrun[jt] * corr + psum;
