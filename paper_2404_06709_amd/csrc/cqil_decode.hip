@@ -61,18 +61,6 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int l = blockIdx.y;
 
-    // one statistic for the whole group: all P layers normalise the same x (Eq.3)
-    float ss = 0.f;
-    for (int k = tid; k < d_model; k += kThreads) {
-        const float v = elem<T>::load(x + k);
-        ss += v * v;
-    }
-    ss = block_sum(ss, scratch);
-    const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
-    const T* g = g_attn + (size_t)l * d_model;
-    for (int k = tid; k < d_model; k += kThreads) xs[k] = elem<T>::load(x + k) * r * elem<T>::load(g + k);
-    __syncthreads();
-
     const int half = d_k >> 1;
     const int pairs_per_head = half / 16;
     const int units = 3 * n_heads * pairs_per_head;   // per layer
@@ -86,13 +74,28 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     const int nkb = d_model / KB;
     const int per = (nkb + ksplit - 1) / ksplit;
     const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
-    float y[2] = {0.f, 0.f};
-    if (on) {
-        const size_t strip_a = ((size_t)(l * 3 + m) * d_model + (size_t)h * d_k + 16 * tp) / 16;
-        const size_t strip_b = strip_a + half / 16;
-        const T* strips[2] = {wqkv + (strip_a * nkb + kb0) * TE, wqkv + (strip_b * nkb + kb0) * TE};
-        tile_strips_dot<T, 2, kU2>(strips, kb1 - kb0, xs + kb0 * KB, y);
+    // the strips of the unit, and their first tiles on the way before the input vector is prepared
+    const size_t strip_a = on ? ((size_t)(l * 3 + m) * d_model + (size_t)h * d_k + 16 * tp) / 16 : 0;
+    const size_t strip_b = strip_a + half / 16;
+    const T* strips[2] = {wqkv + (strip_a * nkb + kb0) * TE, wqkv + (strip_b * nkb + kb0) * TE};
+    const int n_kb = on ? kb1 - kb0 : 0;
+    uint4 wt[2][kU2];
+    tile_strips_prefetch<T, 2, kU2>(strips, n_kb, wt);
+
+    // one statistic for the whole group: all P layers normalise the same x (Eq.3)
+    float ss = 0.f;
+    for (int k = tid; k < d_model; k += kThreads) {
+        const float v = elem<T>::load(x + k);
+        ss += v * v;
     }
+    ss = block_sum(ss, scratch);
+    const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
+    const T* g = g_attn + (size_t)l * d_model;
+    for (int k = tid; k < d_model; k += kThreads) xs[k] = elem<T>::load(x + k) * r * elem<T>::load(g + k);
+    __syncthreads();
+
+    float y[2] = {0.f, 0.f};
+    tile_strips_dot<T, 2, kU2>(strips, n_kb, xs + kb0 * KB, wt, y);
     combine_ksplit<2>(y, ksplit, ul, ks, red);
 
     const int pos = kv_len[0];
@@ -132,9 +135,6 @@ __global__ __launch_bounds__(kThreads) void oproj_kernel(const float* __restrict
     float* red = xs + d_model;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int l = blockIdx.y;
-    const float* c = ctx + (size_t)l * d_model;
-    for (int k = tid; k < d_model; k += kThreads) xs[k] = c[k];
-    __syncthreads();
     const int units = d_model / 16;
     const int uw = kWaves / ksplit;
     const int ul = w / ksplit, ks = w % ksplit;
@@ -144,11 +144,16 @@ __global__ __launch_bounds__(kThreads) void oproj_kernel(const float* __restrict
     const size_t strip_tiles = (size_t)P * nkb;  // tiles of a whole strip
     const int per = (nkb + ksplit - 1) / ksplit;
     const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
+    const T* strips[1] = {wo + ((size_t)(on ? unit : 0) * strip_tiles + (size_t)l * nkb + kb0) * TE};
+    const int n_kb = on ? kb1 - kb0 : 0;
+    uint4 wt[1][kU1];
+    tile_strips_prefetch<T, 1, kU1>(strips, n_kb, wt);  // weights on the way while the input goes to LDS
+
+    const float* c = ctx + (size_t)l * d_model;
+    for (int k = tid; k < d_model; k += kThreads) xs[k] = c[k];
+    __syncthreads();
     float y[1] = {0.f};
-    if (on) {
-        const T* strips[1] = {wo + ((size_t)unit * strip_tiles + (size_t)l * nkb + kb0) * TE};
-        tile_strips_dot<T, 1, kU1>(strips, kb1 - kb0, xs + kb0 * KB, y);
-    }
+    tile_strips_dot<T, 1, kU1>(strips, n_kb, xs + kb0 * KB, wt, y);
     combine_ksplit<1>(y, ksplit, ul, ks, red);
     if (on && ks == 0 && lane < 16) a[(size_t)l * d_model + 16 * unit + lane] = y[0];
 }
@@ -170,6 +175,20 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
     float* scratch = red + kRedFloats;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int l = blockIdx.y;
+    const int units = d_ffn / kGuBlock;
+    const int uw = kWaves / ksplit;
+    const int ul = w / ksplit, ks = w % ksplit;
+    const int unit = blockIdx.x * uw + ul;
+    const bool on = unit < units;
+    const int nkb = d_model / KB;
+    const int per = (nkb + ksplit - 1) / ksplit;
+    const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
+    const size_t strip_g = (size_t)l * 2 * d_ffn / 16 + 2 * (size_t)(on ? unit : 0);  // gate strip; the up strip follows
+    const T* strips[2] = {wgu + (strip_g * nkb + kb0) * TE, wgu + ((strip_g + 1) * nkb + kb0) * TE};
+    const int n_kb = on ? kb1 - kb0 : 0;
+    uint4 wt[2][kU2];
+    tile_strips_prefetch<T, 2, kU2>(strips, n_kb, wt);  // weights on the way while the input is formed
+
     const int jlo = bypass_d < 0 ? l + 1 : max(0, l - bypass_d);  // negative: Eq.5, the input is x alone
     float ss = 0.f;
     for (int k = tid; k < d_model; k += kThreads) {
@@ -184,20 +203,8 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
     for (int k = tid; k < d_model; k += kThreads) xs[k] *= r * elem<T>::load(g + k);
     __syncthreads();
 
-    const int units = d_ffn / kGuBlock;
-    const int uw = kWaves / ksplit;
-    const int ul = w / ksplit, ks = w % ksplit;
-    const int unit = blockIdx.x * uw + ul;
-    const bool on = unit < units;
-    const int nkb = d_model / KB;
-    const int per = (nkb + ksplit - 1) / ksplit;
-    const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
     float y[2] = {0.f, 0.f};
-    if (on) {
-        const size_t strip_g = (size_t)l * 2 * d_ffn / 16 + 2 * (size_t)unit;  // gate strip; the up strip follows
-        const T* strips[2] = {wgu + (strip_g * nkb + kb0) * TE, wgu + ((strip_g + 1) * nkb + kb0) * TE};
-        tile_strips_dot<T, 2, kU2>(strips, kb1 - kb0, xs + kb0 * KB, y);
-    }
+    tile_strips_dot<T, 2, kU2>(strips, n_kb, xs + kb0 * KB, wt, y);
     combine_ksplit<2>(y, ksplit, ul, ks, red);
     if (on && ks == 0 && lane < 16)
         u[(size_t)l * d_ffn + unit * kGuBlock + lane] = y[0] / (1.0f + expf(-y[0])) * y[1];
@@ -220,8 +227,6 @@ __global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict_
     const int slice = blockIdx.y;
     const int k0 = slice * slice_len;
     const int len = min(slice_len, Kp - k0);  // multiple of KB
-    for (int k = tid; k < len; k += kThreads) xs[k] = (k0 + k < K) ? u[k0 + k] : 0.f;
-    __syncthreads();
     const int uw = kWaves / ksplit;
     const int ul = w / ksplit, ks = w % ksplit;
     const int unit = blockIdx.x * uw + ul;
@@ -230,11 +235,15 @@ __global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict_
     const int per = (nkb + ksplit - 1) / ksplit;
     const int kb0 = min(ks * per, nkb), kb1 = min(kb0 + per, nkb);
     const size_t strip_tiles = (size_t)Kp / KB;
+    const T* strips[1] = {wdown + ((size_t)(on ? unit : 0) * strip_tiles + k0 / KB + kb0) * TE};
+    const int n_kb = on ? kb1 - kb0 : 0;
+    uint4 wt[1][kU1];
+    tile_strips_prefetch<T, 1, kU1>(strips, n_kb, wt);  // weights on the way while the input goes to LDS
+
+    for (int k = tid; k < len; k += kThreads) xs[k] = (k0 + k < K) ? u[k0 + k] : 0.f;
+    __syncthreads();
     float y[1] = {0.f};
-    if (on) {
-        const T* strips[1] = {wdown + ((size_t)unit * strip_tiles + k0 / KB + kb0) * TE};
-        tile_strips_dot<T, 1, kU1>(strips, kb1 - kb0, xs + kb0 * KB, y);
-    }
+    tile_strips_dot<T, 1, kU1>(strips, n_kb, xs + kb0 * KB, wt, y);
     combine_ksplit<1>(y, ksplit, ul, ks, red);
     if (on && ks == 0 && lane < 16) part[(size_t)slice * d_model + 16 * unit + lane] = y[0];
 }

@@ -106,9 +106,23 @@ __device__ __forceinline__ int xs_words(int len) { return (len + 511) & ~511; }
 //   strip[s]  first tile of the range of strip s (NS strips advance together, NS * U tiles in flight)
 //   xs        input values of the first column of the range
 // ---------------------------------------------------------------------------------------------------------
+// tile_strips_prefetch issues the loads of the first U tiles of every strip (n_kb <= 0: none) and
+// tile_strips_dot takes them as its first batch: a kernel calls the former before it stages its input vector in
+// LDS (norm, barriers), so that the weight stream starts with the kernel and not after that prologue.
+template <typename T, int NS, int U>
+__device__ __forceinline__ void tile_strips_prefetch(const T* const (&strip)[NS], int n_kb, uint4 (&w)[NS][U]) {
+    constexpr int V = tile<T>::V, TE = tile<T>::kElems;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            w[s][u] = (u < n_kb) ? load16_stream(strip[s] + (size_t)u * TE + lane * V) : make_uint4(0, 0, 0, 0);
+}
+
 template <typename T, int NS, int U>
 __device__ __forceinline__ void tile_strips_dot(const T* const (&strip)[NS], int n_kb, const float* xs,
-                                                float (&out)[NS]) {
+                                                uint4 (&w)[NS][U], float (&out)[NS]) {
     constexpr int V = tile<T>::V, KB = tile<T>::KB, TE = tile<T>::kElems;
     const int lane = threadIdx.x & 63;
     const float* xg = xs + (lane >> 4) * V;
@@ -117,12 +131,13 @@ __device__ __forceinline__ void tile_strips_dot(const T* const (&strip)[NS], int
     for (int s = 0; s < NS; ++s) acc[s] = 0.f;
     for (int kb = 0; kb < n_kb; kb += U) {
         // NS * U tiles in flight; the conditions are wave-uniform (ragged end of the range)
-        uint4 w[NS][U];
+        if (kb > 0) {
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
+            for (int s = 0; s < NS; ++s)
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (kb + u < n_kb) w[s][u] = load16_stream(strip[s] + (size_t)(kb + u) * TE + lane * V);
+                for (int u = 0; u < U; ++u)
+                    if (kb + u < n_kb) w[s][u] = load16_stream(strip[s] + (size_t)(kb + u) * TE + lane * V);
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kb + u < n_kb) {
