@@ -170,7 +170,7 @@ def main() -> int:
                          "decode steps with the partition (p=4, s=21, e=60), against the same layers run one by one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=4)
+    ap.add_argument("--cpu-steps", type=int, default=120)  # about 12 s of oracle work at the 33B shape
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -321,7 +321,7 @@ def main() -> int:
         orc.group_forward(od, np_layers, d_byp, okc, ovc, [S0], xin)          # untimed first touch
         t0 = time.perf_counter()
         for i in range(args.cpu_steps):
-            orc.group_forward(od, np_layers, d_byp, okc, ovc, [S0 + 1 + i], xin)
+            orc.group_forward(od, np_layers, d_byp, okc, ovc, [S0 + 1 + i % args.kv_span], xin)
         cpu_us = (time.perf_counter() - t0) / args.cpu_steps * 1e6
         out["cpu_baseline"] = {"value": round(cpu_us, 1), "unit": "us/token", "cores": orc.num_threads(),
                                "kind": "oracle",
