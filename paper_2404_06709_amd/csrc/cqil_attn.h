@@ -144,9 +144,24 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ x, con
     const int m = blockIdx.y;
     if (o < d_model) {
         const size_t idx = (size_t)m * d_model + o;
+        // the terms are added in a fixed order (x, layers, slices); loads are issued eight at a time so that the
+        // kernel waits for memory a few times, not once per term
         float v = elem<T>::load(x + idx);
-        for (int j = 0; j < P; ++j) v += a[(size_t)j * M * d_model + idx];
-        for (int s = 0; s < n_slices; ++s) v += part[(size_t)s * M * d_model + idx];
+        const size_t stride = (size_t)M * d_model;
+        for (int j0 = 0; j0 < P; j0 += 8) {
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = (j0 + u < P) ? a[(size_t)(j0 + u) * stride + idx] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v += t[u];
+        }
+        for (int s0 = 0; s0 < n_slices; s0 += 8) {
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = (s0 + u < n_slices) ? part[(size_t)(s0 + u) * stride + idx] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v += t[u];
+        }
         elem<T>::store(x_out + idx, v);
     }
     if (advance && m == 0 && blockIdx.x == 0)

@@ -42,7 +42,33 @@ __device__ __forceinline__ void combine_ksplit(float (&y)[NY], int ksplit, int u
             for (int n = 0; n < NY; ++n) y[n] += red[((ul * ksplit + s) * NY + n) * 16 + lane];
     }
 }
-constexpr int kRedFloats = kWaves * 2 * 16;  // [unit in workgroup][ks][NY <= 2][16], units * ksplit = waves
+constexpr int kRedFloats = kWaves * 2 * 16;
+
+// Second half of a norm prologue: xs[k] *= r * g[k] over the row, 16-byte chunks, one or two per thread for the
+// LLaMA widths.  The first chunk of the gain row was requested by the caller before the barriers of its reduction
+// (g0, chunk tid).  Ends with a barrier.
+template <typename T>
+__device__ __forceinline__ void scale_row_in_lds(float* xs, const T* g, const float (&g0)[elem<T>::kVec], float r,
+                                                 int d_model) {
+    constexpr int V = elem<T>::kVec;
+    const int tid = threadIdx.x, n_chunks = d_model / V;
+    for (int c = tid; c < n_chunks; c += kThreads) {
+        float gv[V];
+        if (c == tid) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) gv[e] = g0[e];
+        } else {
+            elem<T>::unpack(load16(g + c * V), gv);
+        }
+#pragma unroll
+        for (int e = 0; e < V; e += 4) {
+            float4 t = *reinterpret_cast<float4*>(xs + c * V + e);
+            t.x *= r * gv[e]; t.y *= r * gv[e + 1]; t.z *= r * gv[e + 2]; t.w *= r * gv[e + 3];
+            *reinterpret_cast<float4*>(xs + c * V + e) = t;
+        }
+    }
+    __syncthreads();
+}  // [unit in workgroup][ks][NY <= 2][16], units * ksplit = waves
 
 // ---------------------------------------------------------------------------------------------------------
 // 1. RMSNorm + QKV projection + rotary embedding + KV append.  grid = (unit blocks, P); a unit is the pair of
@@ -83,16 +109,23 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     tile_strips_prefetch<T, 2, kU2>(strips, n_kb, wt);
 
     // one statistic for the whole group: all P layers normalise the same x (Eq.3)
-    float ss = 0.f;
-    for (int k = tid; k < d_model; k += kThreads) {
-        const float v = elem<T>::load(x + k);
-        ss += v * v;
-    }
-    ss = block_sum(ss, scratch);
-    const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
+    constexpr int V = elem<T>::kVec;
+    const int n_chunks = d_model / V;
     const T* g = g_attn + (size_t)l * d_model;
-    for (int k = tid; k < d_model; k += kThreads) xs[k] = elem<T>::load(x + k) * r * elem<T>::load(g + k);
-    __syncthreads();
+    float ss = 0.f;
+    for (int c = tid; c < n_chunks; c += kThreads) {
+        float v[V];
+        elem<T>::unpack(load16(x + c * V), v);
+#pragma unroll
+        for (int e = 0; e < V; e += 4) {
+            *reinterpret_cast<float4*>(xs + c * V + e) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
+            ss += v[e] * v[e] + v[e + 1] * v[e + 1] + v[e + 2] * v[e + 2] + v[e + 3] * v[e + 3];
+        }
+    }
+    float g0[V];  // requested before the reduction's barriers, used after them
+    elem<T>::unpack(load16(g + min(tid, n_chunks - 1) * V), g0);
+    ss = block_sum(ss, scratch);
+    scale_row_in_lds<T>(xs, g, g0, 1.0f / sqrtf(ss / (float)d_model + eps), d_model);
 
     float y[2] = {0.f, 0.f};
     tile_strips_dot<T, 2, kU2>(strips, n_kb, xs + kb0 * KB, wt, y);
@@ -150,7 +183,8 @@ __global__ __launch_bounds__(kThreads) void oproj_kernel(const float* __restrict
     tile_strips_prefetch<T, 1, kU1>(strips, n_kb, wt);  // weights on the way while the input goes to LDS
 
     const float* c = ctx + (size_t)l * d_model;
-    for (int k = tid; k < d_model; k += kThreads) xs[k] = c[k];
+    for (int k = 4 * tid; k < d_model; k += 4 * kThreads)
+        *reinterpret_cast<float4*>(xs + k) = *reinterpret_cast<const float4*>(c + k);
     __syncthreads();
     float y[1] = {0.f};
     tile_strips_dot<T, 1, kU1>(strips, n_kb, xs + kb0 * KB, wt, y);
@@ -190,18 +224,31 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
     tile_strips_prefetch<T, 2, kU2>(strips, n_kb, wt);  // weights on the way while the input is formed
 
     const int jlo = bypass_d < 0 ? l + 1 : max(0, l - bypass_d);  // negative: Eq.5, the input is x alone
-    float ss = 0.f;
-    for (int k = tid; k < d_model; k += kThreads) {
-        float hv = elem<T>::load(x + k);
-        for (int j = jlo; j <= l; ++j) hv += a[(size_t)j * d_model + k];
-        xs[k] = hv;
-        ss += hv * hv;
-    }
-    ss = block_sum(ss, scratch);
-    const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
+    constexpr int V = elem<T>::kVec;
+    const int n_chunks = d_model / V;
     const T* g = g_ffn + (size_t)l * d_model;
-    for (int k = tid; k < d_model; k += kThreads) xs[k] *= r * elem<T>::load(g + k);
-    __syncthreads();
+    float ss = 0.f;
+    for (int c = tid; c < n_chunks; c += kThreads) {
+        float hv[V];
+        elem<T>::unpack(load16(x + c * V), hv);
+        for (int j = jlo; j <= l; ++j) {
+            const float* ap = a + (size_t)j * d_model + c * V;
+#pragma unroll
+            for (int e = 0; e < V; e += 4) {
+                const float4 t = *reinterpret_cast<const float4*>(ap + e);
+                hv[e] += t.x; hv[e + 1] += t.y; hv[e + 2] += t.z; hv[e + 3] += t.w;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < V; e += 4) {
+            *reinterpret_cast<float4*>(xs + c * V + e) = make_float4(hv[e], hv[e + 1], hv[e + 2], hv[e + 3]);
+            ss += hv[e] * hv[e] + hv[e + 1] * hv[e + 1] + hv[e + 2] * hv[e + 2] + hv[e + 3] * hv[e + 3];
+        }
+    }
+    float g0[V];  // requested before the reduction's barriers, used after them
+    elem<T>::unpack(load16(g + min(tid, n_chunks - 1) * V), g0);
+    ss = block_sum(ss, scratch);
+    scale_row_in_lds<T>(xs, g, g0, 1.0f / sqrtf(ss / (float)d_model + eps), d_model);
 
     float y[2] = {0.f, 0.f};
     tile_strips_dot<T, 2, kU2>(strips, n_kb, xs + kb0 * KB, wt, y);
@@ -240,7 +287,10 @@ __global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict_
     uint4 wt[1][kU1];
     tile_strips_prefetch<T, 1, kU1>(strips, n_kb, wt);  // weights on the way while the input goes to LDS
 
-    for (int k = tid; k < len; k += kThreads) xs[k] = (k0 + k < K) ? u[k0 + k] : 0.f;
+    for (int k = 4 * tid; k < len; k += 4 * kThreads) {  // len and K are multiples of 4
+        const float4 t = (k0 + k < K) ? *reinterpret_cast<const float4*>(u + k0 + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        *reinterpret_cast<float4*>(xs + k) = t;
+    }
     __syncthreads();
     float y[1] = {0.f};
     tile_strips_dot<T, 1, kU1>(strips, n_kb, xs + kb0 * KB, wt, y);
