@@ -42,8 +42,18 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
     float qv[V];
     {
         const QT* qp = q + (size_t)l * q_ls + (size_t)m * q_ms + (size_t)h * DK + sub * V;
+        float qr[V];
+        if constexpr (sizeof(QT) * V == 16) {
+            elem<QT>::unpack(load16(qp), qr);   // same element type as the cache: one 16-byte load
+        } else {
 #pragma unroll
-        for (int j = 0; j < V; ++j) qv[j] = elem<QT>::load(qp + j) * scale;
+            for (int j = 0; j < V; j += 4) {    // fp32 queries: 16-byte loads
+                const float4 t = *reinterpret_cast<const float4*>(qp + j);
+                qr[j] = t.x; qr[j + 1] = t.y; qr[j + 2] = t.z; qr[j + 3] = t.w;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < V; ++j) qv[j] = qr[j] * scale;
     }
     const size_t head_off = (((size_t)l * b_max + b) * n_heads + h) * (size_t)max_seq * DK;
     const T* kb = kc + head_off + sub * V;

@@ -107,6 +107,10 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     const int n_kb = on ? kb1 - kb0 : 0;
     uint4 wt[2][kU2];
     tile_strips_prefetch<T, 2, kU2>(strips, n_kb, wt);
+    // the position and the rotation of the epilogue are requested now, not after the dot products
+    const int pos = kv_len[0];
+    float2 cs = make_float2(1.f, 0.f);
+    if (on && ks == 0 && lane < 16 && m < 2 && pos >= 0 && pos < max_seq) cs = rope[(size_t)pos * half + 16 * tp + lane];
 
     // one statistic for the whole group: all P layers normalise the same x (Eq.3)
     constexpr int V = elem<T>::kVec;
@@ -131,7 +135,6 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     tile_strips_dot<T, 2, kU2>(strips, n_kb, xs + kb0 * KB, wt, y);
     combine_ksplit<2>(y, ksplit, ul, ks, red);
 
-    const int pos = kv_len[0];
     if (on && ks == 0 && lane < 16 && pos >= 0 && pos < max_seq) {
         const int e = 16 * tp + lane;  // rotary pair (e, e + half)
         const float a = y[0], b = y[1];
@@ -140,7 +143,6 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
             elem<T>::store(dst + e, a);
             elem<T>::store(dst + e + half, b);
         } else {
-            const float2 cs = rope[(size_t)pos * half + e];
             const float ra = a * cs.x - b * cs.y, rb = b * cs.x + a * cs.y;
             if (m == 0) {
                 float* dst = q_out + (size_t)l * d_model + (size_t)h * d_k;
