@@ -38,7 +38,8 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
     if (S < 1) return;
 
     const size_t d_model = (size_t)n_heads * DK;
-    const float scale = 1.0f / sqrtf((float)DK);
+    // scores are kept in units of log 2 (scale = log2 e / sqrt(d_k)): the exponentials are single exp2 instructions
+    const float scale = 1.4426950408889634f / sqrtf((float)DK);
     float qv[V];
     {
         const QT* qp = q + (size_t)l * q_ls + (size_t)m * q_ms + (size_t)h * DK + sub * V;
@@ -84,20 +85,19 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
             elem<T>::unpack(kraw[u], f);
 #pragma unroll
             for (int j = 0; j < V; ++j) dot = fmaf(f[j], qv[j], dot);
-#pragma unroll
-            for (int off = LPS / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, kWave);
+            dot = lane_group_sum<LPS>(dot);
             sc[u] = ok[u] ? dot : -INFINITY;
             mloc = fmaxf(mloc, sc[u]);
         }
         const float nm = fmaxf(mx, mloc);
         if (nm > -INFINITY) {
-            const float corr = expf(mx - nm);  // exp(-inf) = 0 the first time
+            const float corr = __builtin_amdgcn_exp2f(mx - nm);  // exp2(-inf) = 0 the first time
             lsum *= corr;
 #pragma unroll
             for (int j = 0; j < V; ++j) acc[j] *= corr;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const float p = ok[u] ? expf(sc[u] - nm) : 0.f;
+                const float p = ok[u] ? __builtin_amdgcn_exp2f(sc[u] - nm) : 0.f;
                 float f[V];
                 elem<T>::unpack(vraw[u], f);
                 lsum += p;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
     float wm = mx;
 #pragma unroll
     for (int off = LPS; off < kWave; off <<= 1) wm = fmaxf(wm, __shfl_xor(wm, off, kWave));
-    const float sc0 = (mx == -INFINITY) ? 0.f : expf(mx - wm);
+    const float sc0 = (mx == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mx - wm);
     lsum *= sc0;
 #pragma unroll
     for (int j = 0; j < V; ++j) acc[j] *= sc0;
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
         float Ls = 0.f, c = 0.f;
 #pragma unroll
         for (int i = 0; i < NW; ++i) {
-            const float e = (red_m[i] == -INFINITY) ? 0.f : expf(red_m[i] - gm);
+            const float e = (red_m[i] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(red_m[i] - gm);
             Ls += e * red_l[i];
             c += e * accs[i][tid];
         }

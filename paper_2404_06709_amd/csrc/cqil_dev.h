@@ -68,6 +68,23 @@ __device__ __forceinline__ uint4 load16_stream(const void* p) {
 }
 __device__ __forceinline__ uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 
+// Sum over aligned groups of G consecutive lanes (G = 2 .. 32, a power of two); every lane returns its group's total.
+// Up to 16 lanes the partner values come through the ALU's data-parallel lane permutes (within quads: lane ^ 1,
+// lane ^ 2; then the mirror of each half row and of each row of 16), not through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int G>
+__device__ __forceinline__ float lane_group_sum(float v) {
+    if (G >= 2) v += dpp_move<0xB1>(v);    // quad_perm [1, 0, 3, 2]
+    if (G >= 4) v += dpp_move<0x4E>(v);    // quad_perm [2, 3, 0, 1]
+    if (G >= 8) v += dpp_move<0x141>(v);   // row_half_mirror
+    if (G >= 16) v += dpp_move<0x140>(v);  // row_mirror
+    if (G >= 32) v += __shfl_xor(v, 16, kWave);
+    return v;
+}
+
 // Sum over the 64 lanes of a wave; every lane returns the total.
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
