@@ -217,6 +217,21 @@ def test_every_bypass_distance_decode_and_prefill(P, dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("head_dim", [32, 256])
+def test_smallest_and_largest_head_sizes(head_dim, dtype):
+    """Head sizes at both ends of what the attention kernels take (4 and 32 lanes per cache slot for bf16 heads of
+    32 and 256; 8 lanes for fp32 heads of 32): single-token decode, a batch of decode rows and a short prefill."""
+    if head_dim * (4 if dtype == torch.float32 else 2) // 16 > 32:
+        pytest.skip("fp32 heads of 256 need 64 lanes per slot: rejected by the library (see test_boundary)")
+    shape = synth.Shape(4 * head_dim, 4, head_dim, 16 * 24)
+    pair = Pair(shape, 2, dtype, max_seq=200, b_max=3, seed=2200 + head_dim, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([150, 0, 37], seed=14)
+    pair.step(pair.hidden(1, 1, seed=1), 1, label=f"d_k={head_dim} decode {dtype}")
+    pair.step(pair.hidden(3, 1, seed=2), 1, label=f"d_k={head_dim} batch of 3 {dtype}")
+    pair.step(pair.hidden(2, 5, seed=3), 0, label=f"d_k={head_dim} prefill {dtype}")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_group_wider_than_eight_layers(dtype):
     """Ten layers in one group: beyond the eight whose attention outputs the bypass kernel keeps in registers, so
     the general kernel of the token-parallel path (and the decode kernels at P = 10) are the ones checked."""
