@@ -323,6 +323,164 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Up to 32 token rows (a batch of decode rows): the product is a weight stream.  A workgroup of 4 waves owns 64
+// weight rows; the waves split its K range four ways and never meet before the end: every wave fetches its own
+// weight fragments and its own activation fragments (32 rows x 16 columns straight from global memory, they stay
+// in L2) a ring of kRowsRing slabs ahead, no LDS staging, no barrier in the loop.  The four partial tiles are
+// added through LDS in wave order; wave w then finishes rows 8 (w & 1) + {0..7 of 16, and the 8 rows 16 further}
+// of row block w >> 1 (for SwiGLU that is a gate quad and its up quad).  Many small workgroups (ten or more
+// waves per SIMD pair fit) keep far more bytes in flight per CU than the tiled kernel's two workgroups.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kRowsRing = 4;
+template <typename CT, int EPI>
+__global__ __launch_bounds__(256) void gemm_rows_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, CT* __restrict__ C, const float* __restrict__ R, int M,
+    int N, int K, size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t strip_step, size_t ktile_step,
+    size_t sC, int ksplit, float* __restrict__ part) {
+    constexpr int TE = 512;
+    __shared__ __align__(16) float red[4][32][64];   // [wave][accumulator register][lane]
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int fi = lane & 31, fgg = lane >> 5;
+    const int nx = (N + 63) / 64;
+    const int nt = blockIdx.x % nx, zk = blockIdx.x / nx;
+    const int z = zk / ksplit, ks = zk % ksplit;
+    if (z >= groups) return;
+    A += (size_t)z * sA;
+    C += (size_t)z * sC;
+    const int n0 = nt * 64;
+    const size_t w_tiles_per_strip = Kp / 32;
+    const int n_strips = (N + 15) / 16;
+    const int n_k16 = 2 * (int)((K + 31) / 32);
+    // slabs of this workgroup's K slice, then of this wave's quarter of it
+    const int per_slice = (n_k16 + ksplit - 1) / ksplit;
+    const int g0 = min(ks * per_slice, n_k16), g1 = min(g0 + per_slice, n_k16);
+    const int per_wave = (g1 - g0 + 3) / 4;
+    const int k0 = min(g0 + w * per_wave, g1), k1 = min(k0 + per_wave, g1);
+
+    const bf16_t* wbase = W + (((size_t)z * strip_step + n0 / 16) * w_tiles_per_strip + (size_t)z * ktile_step) * TE;
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(wbase), 0, kGemmBufRange, kGemmBufFlags);
+    const __amdgpu_buffer_rsrc_t arsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, kGemmBufRange, kGemmBufFlags);
+    uint32_t wvo[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int rel = min(2 * s + (fi >> 4), n_strips - 1 - n0 / 16);
+        wvo[s] = (uint32_t)(((size_t)rel * w_tiles_per_strip * TE + (fgg * 16 + (fi & 15)) * 8) * 2);
+    }
+    const uint32_t avo = (uint32_t)(((size_t)min(fi, M - 1) * lda + 8 * fgg) * 2);
+
+    gemm_u32x4 wf[kRowsRing][2], af[kRowsRing];
+    auto request = [&](int slot, int k16) {
+        const int kc = min(k16, n_k16 - 1);
+        // activation columns past K (inside the last 32-column tile) are read from the last piece of the row
+        // and dropped below; the weights there are the packer's zero padding
+        const int col = min(16 * kc + 8 * fgg, K - 8);
+        af[slot] = __builtin_amdgcn_raw_buffer_load_b128(arsrc, avo + (uint32_t)(2 * (col - 8 * fgg)), 0, 0);
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+            wf[slot][s] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wvo[s], (uint32_t)kc * 512u, 2);  // streamed once
+    };
+    gemm_f32x16 acc[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < kRowsRing; ++i) request(i, k0 + i);
+    for (int kb = k0; kb < k1; kb += kRowsRing) {
+#pragma unroll
+        for (int i = 0; i < kRowsRing; ++i) {
+            if (kb + i < k1) {  // wave-uniform
+                gemm_u32x4 a = af[i];
+                if (16 * (kb + i) + 8 * fgg >= K) a = gemm_u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+                    acc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(gemm_bf16x8, wf[i][s]),
+                                                                     __builtin_bit_cast(gemm_bf16x8, a), acc[s], 0, 0, 0);
+                if (kb + i + kRowsRing < k1) request(i, kb + i + kRowsRing);
+            }
+        }
+    }
+    // ---- the four K quarters meet: partial tiles through LDS, added in wave order
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[w][16 * s + r][lane] = acc[s][r];
+    __syncthreads();
+    const int s_out = w >> 1, qp = w & 1;   // this wave finishes registers 4 qp .. + 3 and 4 (qp + 2) .. + 3 of block s_out
+    float v[2][4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int reg = 16 * s_out + 4 * (qp + 2 * half) + e;
+            v[half][e] = ((red[0][reg][lane] + red[1][reg][lane]) + red[2][reg][lane]) + red[3][reg][lane];
+        }
+    const int m = fi;
+    if (m >= M) return;
+    const int nb = n0 + 32 * s_out;  // first weight row of the block
+    if (ksplit > 1) {  // partial sums of this K slice: part[ks][z][m][n], fp32; gemm_reduce_kernel finishes
+        float* pz = part + ((size_t)ks * groups + z) * (size_t)M * N;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int n = nb + 8 * (qp + 2 * half) + 4 * fgg;
+            if (n < N) *reinterpret_cast<float4*>(pz + (size_t)m * N + n) = make_float4(v[half][0], v[half][1], v[half][2], v[half][3]);
+        }
+        return;
+    }
+    if (EPI == kEpiSwiglu) {
+        const int n = nb + 8 * qp + 4 * fgg;  // gate row; its up row is 16 further
+        if (n < N) {
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = v[0][e] / (1.0f + __expf(-v[0][e])) * v[1][e];
+            gemm_store4(C + (size_t)m * ldc + nb / 2 + 8 * qp + 4 * fgg, o);
+        }
+    } else {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int n = nb + 8 * (qp + 2 * half) + 4 * fgg;
+            if (n >= N) continue;
+            float o[4] = {v[half][0], v[half][1], v[half][2], v[half][3]};
+            if (EPI == kEpiAddR) {
+                const float4 r = *reinterpret_cast<const float4*>(R + (size_t)m * N + n);
+                o[0] += r.x; o[1] += r.y; o[2] += r.z; o[3] += r.w;
+            }
+            gemm_store4(C + (size_t)m * ldc + n, o);
+        }
+    }
+}
+
+template <typename CT, int EPI>
+static hipError_t gemm_rows_launch(const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K,
+                                   size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step,
+                                   size_t k_step, size_t sC, float* part, size_t part_floats, hipStream_t st) {
+    const int nx = (N + 63) / 64;
+    const long tiles = (long)nx * groups;
+    const int n_k16 = 2 * ((K + 31) / 32);
+    // K slices across workgroups until about five workgroups per CU exist (each wave keeps at least 8 slabs)
+    int ksplit = 1;
+    if (EPI != kEpiSwiglu && part != nullptr) {
+        const size_t per_slice = (size_t)groups * M * N;
+        while (ksplit < 16 && tiles * ksplit < 1024 && n_k16 / (ksplit * 2 * 4) >= 8 &&
+               per_slice * (size_t)(ksplit * 2) <= part_floats)
+            ksplit *= 2;
+    }
+    const long wgs = tiles * ksplit;
+    if (wgs > 0x7fffffffL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_rows_kernel<CT, EPI>), dim3((unsigned)wgs), dim3(256), 0, st, A, W, C, R, M, N, K,
+                       lda, Kp, ldc, groups, sA, n_step / 16, k_step / 32, sC, ksplit, part);
+    if (ksplit > 1) {
+        const size_t total = (size_t)groups * M * N / 4;
+        const unsigned g = (unsigned)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_reduce_kernel<CT, EPI>), dim3(g), dim3(256), 0, st, part, C, R, M, N, ldc,
+                           groups, sC, ksplit);
+    }
+    return hipSuccess;
+}
+
 // Same argument convention as the plain kernel of the token-parallel path: n_step / k_step are the group strides
 // in weight rows / columns (multiples of 16 / 32).  part / part_floats: scratch for split-K partial sums (may be
 // null / 0): when the tile grid is too small to fill the chip, K is cut into slices of whole 64-column steps,
@@ -367,7 +525,7 @@ static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, cons
     return hipSuccess;
 }
 
-// tile: 1 = 256 tokens x 256 rows (8 waves), 2 = 128 x 256 (4 waves); 0 = default
+// tile: 1 = 256 tokens x 256 rows (8 waves), 2 = 128 x 256 (4 waves) also for few rows; 0 = default
 template <typename CT, int EPI>
 static hipError_t gemm_mfma(int tile_sel, const bf16_t* A, const bf16_t* W, CT* C, const float* R, int M, int N, int K,
                             size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step,
@@ -375,8 +533,14 @@ static hipError_t gemm_mfma(int tile_sel, const bf16_t* A, const bf16_t* W, CT* 
     if (M < 1 || (N & 3) || (K & 7) || K < 8) return hipErrorInvalidValue;
     if (Kp >= (1u << 21) || lda >= (1u << 21)) return hipErrorInvalidValue;  // byte offsets of a tile stay below 2 GiB
     // default: 128 x 256 (two workgroups per CU overlap each other's barriers and load latency)
-    // up to 32 token rows (a batch of decode rows): one 32-token tile per wave, a quarter of the matrix-core and LDS
-    // work per weight byte streamed
+    // up to 8 token rows, plain and residual epilogues (QKV, O, down): the barrier-free streaming kernel.  Measured at
+    // the 13B shape, P = 4, against the tiled kernel with one 32-token tile per wave: O projection 34 against 41 us,
+    // down 85 against 95, QKV 99 against 98 + 5 for the K-slice reduction it needs; from 16 rows on the per-wave
+    // activation fragments cost more than the barriers saved (QKV 125 against 102 us), and the gate/up product is
+    // faster tiled at every row count (166 against 170 us).  tile_sel 2 forces the tiled kernel.
+    if (M <= 8 && EPI != kEpiSwiglu && tile_sel != 2)
+        return gemm_rows_launch<CT, EPI>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, part,
+                                         part_floats, st);
     if (M <= 32)
         return gemm_mfma_launch<CT, EPI, 1, 4, 1>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, part,
                                                   part_floats, st);
