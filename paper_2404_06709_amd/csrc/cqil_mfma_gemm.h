@@ -460,11 +460,12 @@ static hipError_t gemm_rows_launch(const bf16_t* A, const bf16_t* W, CT* C, cons
     const int nx = (N + 63) / 64;
     const long tiles = (long)nx * groups;
     const int n_k16 = 2 * ((K + 31) / 32);
-    // K slices across workgroups until about five workgroups per CU exist (each wave keeps at least 8 slabs)
+    // K slices across workgroups until about a thousand workgroups (15 waves per CU) exist; a wave keeps 8 slabs or
+    // more.  (13B, 8 rows: O projection 35 us with 1280 workgroups, 41 us with 640.)
     int ksplit = 1;
     if (EPI != kEpiSwiglu && part != nullptr) {
         const size_t per_slice = (size_t)groups * M * N;
-        while (ksplit < 16 && tiles * ksplit < 1024 && n_k16 / (ksplit * 2 * 4) >= 8 &&
+        while (ksplit < 16 && tiles * ksplit < 960 && n_k16 / (ksplit * 2 * 4) >= 8 &&
                per_slice * (size_t)(ksplit * 2) <= part_floats)
             ksplit *= 2;
     }
