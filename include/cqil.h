@@ -196,9 +196,10 @@ int cqil_model_forward(cqil_model *m /* host */, const int32_t *tokens, int B, i
  * of work and split its k range in the QKV / O / gate-up / down kernel: 1, 2, 4 or 8; 0 = chosen by shape),
  * "down_slice_max" (longest K slice of the down projection, multiple of 512, at
  * most 12288): single-token decode kernels.  "gemm_tile" (workgroup tile of the bf16 matrix-core GEMM of the
- * token-parallel path: 1 = 256 tokens x 256 weight rows, 2 = 128 x 256; 0 = default).  The k split
- * and the number of K slices change the order in which partial sums are added, nothing else; the GEMM tile changes
- * no result at all.  Unknown key or bad value: CQIL_EINVAL. */
+ * token-parallel path: 1 = 256 tokens x 256 weight rows, 2 = 128 x 256 and the tiled kernel also for up to 8 token
+ * rows, where the default is a barrier-free streaming kernel; 0 = default).  The k split, the number of K slices and,
+ * for up to 8 rows, the choice between the two GEMM kernels change the order in which partial sums are added, nothing
+ * else; for more rows the GEMM tile changes no result at all.  Unknown key or bad value: CQIL_EINVAL. */
 int cqil_set_tuning(const char *key, int value);
 
 /* Library build information (host-only). */
