@@ -25,7 +25,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
 # what the same counters read for a plain copy kernel (profiles/decode_step_33b_P4_B1_hbm_traffic.md).  Only valid
 # for the workload it was measured on; other workloads report null.
-MEASURED_TRAFFIC = {("33b", 4, "gateup"): 1_909_963_583}
+MEASURED_TRAFFIC = {("33b", 4, "gateup"): 1_909_967_600}
 
 
 def kernel_bytes(shape, P, lens, es=2):
