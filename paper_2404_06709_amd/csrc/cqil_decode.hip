@@ -329,8 +329,8 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
         while (ks < 8 && units * ks < want_waves) ks *= 2;
         return ks;
     };
-    const int ks_q = g_tune.ksplit_qkv ? g_tune.ksplit_qkv : split_for(3L * nh * (dk / 32) * P, 8192);
-    const int ks_o = g_tune.ksplit_o ? g_tune.ksplit_o : (narrow ? (P >= 4 ? 2 : 8) : (P >= 4 ? 1 : (P >= 2 ? 2 : 4)));
+    const int ks_q = g_tune.ksplit_qkv ? g_tune.ksplit_qkv : split_for(3L * nh * (dk / 32) * P, 6144);
+    const int ks_o = g_tune.ksplit_o ? g_tune.ksplit_o : (narrow ? (P >= 4 ? 4 : 8) : (P >= 4 ? 1 : (P >= 2 ? 2 : 4)));
     const int ks_g = g_tune.ksplit_gu ? g_tune.ksplit_gu : (narrow ? ((P == 2 || P == 3) ? 4 : 2) : split_for((long)(f / kGuBlock) * P, 16384));
     const size_t lds_x = ((size_t)dm + kRedFloats + 16) * sizeof(float);
 
