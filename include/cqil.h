@@ -72,9 +72,9 @@ typedef struct {
     void *k, *v;
     int32_t *kv_len; /* [b_max] tokens already cached per sequence; the same for all P layers */
     int b_max;
-    int max_kv_len;  /* host-side upper bound of kv_len[b] before the call: used for the range check
-                        and to size launches (kernels read exact lengths from kv_len and never write
-                        past max_seq even if this bound is wrong).  Advanced with kv_len. */
+    int max_kv_len;  /* host-side upper bound of kv_len[b] before the call, used only for the host's range
+                        check max_kv_len + T <= max_seq (kernels read the exact lengths from kv_len and
+                        never write past max_seq even if this bound is wrong).  Advanced with kv_len. */
 } cqil_kv;
 
 /* Byte offsets of the parts of a packed group (all multiples of 256).  Logical matrices:
@@ -183,7 +183,8 @@ typedef struct {
 
 size_t cqil_model_workspace_bytes(const cqil_model *m /* host */, int B, int T);
 
-/* tokens [B][T] int32 -> groups in order -> final norm of the last position -> logits -> greedy token
+/* tokens [B][T] int32 (device; an id outside 0 .. vocab-1 is clamped to that range by the embedding gather, never
+ * read out of the table) -> groups in order -> final norm of the last position -> logits -> greedy token
  * (lowest index among equal maxima).  hidden_out (optional) [B][T][d_model] dtype is the state after
  * the last layer; logits_out (optional) [B][vocab] fp32; next_token_out (optional) [B] int32.
  * kv_len and m->max_kv_len advance by T when advance_kv_len != 0. */

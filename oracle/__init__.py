@@ -221,6 +221,26 @@ def group_forward(dims: Dims, layers: Sequence[dict], d: int, kcache, vcache, kv
     return (out, da, dh) if debug else out
 
 
+def group_forward_rows(dims: Dims, layers: Sequence[dict], d: int, kcache, vcache, kv_len, x, rows):
+    """group_forward with the outputs restricted to the rows flagged in ``rows`` [B, T] (bool): keys and values
+    of every row are cached, the flagged rows of (x_out, attn, h) equal those of the full call, the rest are 0."""
+    x = _f64(x)
+    B, T, dm = x.shape
+    P = len(layers)
+    assert kcache.shape[0] >= P and kcache.dtype == np.float64 and kcache.flags.c_contiguous
+    arr, keep = _layers(layers, dims.wdtype)
+    kv = np.ascontiguousarray(kv_len, dtype=np.int32)
+    flags = np.ascontiguousarray(np.asarray(rows).reshape(B, T), dtype=np.uint8)
+    out = np.empty_like(x)
+    da = np.empty((P, B, T, dm))
+    dh = np.empty((P, B, T, dm))
+    rc = lib().orc_group_forward_rows(C.byref(dims.c()), P, d, arr, _p(kcache), _p(vcache), kcache.shape[1],
+                                      _p(kv), _p(x), _p(out), B, T, _p(flags), _p(da), _p(dh))
+    if rc:
+        raise RuntimeError(f"orc_group_forward_rows rc={rc}")
+    return out, da, dh
+
+
 def bypass_transfers(p: int, d: int) -> int:
     return int(lib().orc_bypass_transfers(p, d))
 

@@ -157,9 +157,14 @@ static size_t cache_index(const orc_dims *D, int b_max, int layer_in_group, int 
  *                   the rotary embedding), earlier slots are read.
  *   a_out   [B][T][d_model] = Concat(heads) W^O
  * Position t of sequence b attends slots 0 .. kv_len[b]+t (causal).
+ * rows (may be NULL = every row): [B][T] flags.  A row whose flag is 0 still has its key and value computed
+ * and cached (later rows attend them), but its query, attention and output are skipped and its a_out row is
+ * left untouched: the outputs of the flagged rows are exactly those of the full call (Eq.2: an output row
+ * depends on other rows only through their keys and values).  Used to sample rows of long prefills.
  */
-int orc_attn_module(const orc_dims *D, const orc_layer *L, int lg, double *kcache, double *vcache,
-                    int b_max, const int32_t *kv_len, const double *x, int B, int T, double *a_out) {
+static int attn_module_rows(const orc_dims *D, const orc_layer *L, int lg, double *kcache, double *vcache,
+                            int b_max, const int32_t *kv_len, const double *x, int B, int T,
+                            const unsigned char *rows, double *a_out) {
     const int dm = D->d_model, nh = D->n_heads, dk = D->head_dim;
     if (nh * dk != dm || (dk & 1)) return -1;
     double *nrm = malloc(sizeof(double) * (size_t)dm);
@@ -173,17 +178,19 @@ int orc_attn_module(const orc_dims *D, const orc_layer *L, int lg, double *kcach
         for (int t = 0; t < T; ++t) {
             const double *xt = x + ((size_t)b * (size_t)T + (size_t)t) * (size_t)dm;
             long pos = (long)kv_len[b] + t;
+            const int want = !rows || rows[(size_t)b * (size_t)T + (size_t)t];
             orc_rmsnorm(xt, L->g_attn, D->wdtype, dm, D->rms_eps, nrm);
-            orc_linear(L->wq, D->wdtype, dm, dm, nrm, q);
+            if (want) orc_linear(L->wq, D->wdtype, dm, dm, nrm, q);
             orc_linear(L->wk, D->wdtype, dm, dm, nrm, k);
             orc_linear(L->wv, D->wdtype, dm, dm, nrm, v);
 #pragma omp parallel for schedule(static)
             for (int h = 0; h < nh; ++h) {
                 double *qh = q + (size_t)h * dk, *kh = k + (size_t)h * dk, *vh = v + (size_t)h * dk;
-                orc_rope(qh, dk, pos, D->rope_base);
                 orc_rope(kh, dk, pos, D->rope_base);
                 memcpy(kcache + cache_index(D, b_max, lg, b, h, pos), kh, sizeof(double) * (size_t)dk);
                 memcpy(vcache + cache_index(D, b_max, lg, b, h, pos), vh, sizeof(double) * (size_t)dk);
+                if (!want) continue;
+                orc_rope(qh, dk, pos, D->rope_base);
                 /* softmax(q K^T / sqrt(d_k)) V over slots 0..pos */
                 double *sc = malloc(sizeof(double) * (size_t)(pos + 1));
                 double mx = -INFINITY;
@@ -206,12 +213,18 @@ int orc_attn_module(const orc_dims *D, const orc_layer *L, int lg, double *kcach
                 }
                 free(sc);
             }
-            orc_linear(L->wo, D->wdtype, dm, dm, ctx,
-                       a_out + ((size_t)b * (size_t)T + (size_t)t) * (size_t)dm);
+            if (want)
+                orc_linear(L->wo, D->wdtype, dm, dm, ctx,
+                           a_out + ((size_t)b * (size_t)T + (size_t)t) * (size_t)dm);
         }
     }
     free(nrm); free(q); free(k); free(v); free(ctx);
     return 0;
+}
+
+int orc_attn_module(const orc_dims *D, const orc_layer *L, int lg, double *kcache, double *vcache,
+                    int b_max, const int32_t *kv_len, const double *x, int B, int T, double *a_out) {
+    return attn_module_rows(D, L, lg, kcache, vcache, b_max, kv_len, x, B, T, NULL, a_out);
 }
 
 /* FFN_l(h) for M token vectors (Eq.2 with SwiGLU): Wdown( silu(Wgate n) * (Wup n) ), n = Norm(h) */
@@ -259,18 +272,39 @@ int orc_seq_layer(const orc_dims *D, const orc_layer *L, double *kcache, double 
  * dbg_attn, dbg_h: optional [P][B][T][d_model] copies of attn_i and h_i (may be NULL).
  * kv_len is not advanced here.
  */
+static int group_forward_rows(const orc_dims *D, int P, int d, const orc_layer *layers, double *kcache,
+                              double *vcache, int b_max, const int32_t *kv_len, const double *x, double *x_out,
+                              int B, int T, const unsigned char *rows, double *dbg_attn, double *dbg_h);
+
 int orc_group_forward(const orc_dims *D, int P, int d, const orc_layer *layers, double *kcache,
                       double *vcache, int b_max, const int32_t *kv_len, const double *x, double *x_out,
                       int B, int T, double *dbg_attn, double *dbg_h) {
+    return group_forward_rows(D, P, d, layers, kcache, vcache, b_max, kv_len, x, x_out, B, T, NULL, dbg_attn, dbg_h);
+}
+
+/* The same step with the outputs restricted to the rows whose flag in rows[B][T] is non-zero: every row's keys and
+ * values are computed and cached, the flagged rows of x_out / dbg_attn / dbg_h are exactly those of the full call,
+ * the other rows of the outputs are zero.  The feed-forward module acts on each row alone (Eq.2), so skipping a
+ * row changes no other row. */
+int orc_group_forward_rows(const orc_dims *D, int P, int d, const orc_layer *layers, double *kcache,
+                           double *vcache, int b_max, const int32_t *kv_len, const double *x, double *x_out,
+                           int B, int T, const unsigned char *rows, double *dbg_attn, double *dbg_h) {
+    if (!rows) return -1;
+    return group_forward_rows(D, P, d, layers, kcache, vcache, b_max, kv_len, x, x_out, B, T, rows, dbg_attn, dbg_h);
+}
+
+static int group_forward_rows(const orc_dims *D, int P, int d, const orc_layer *layers, double *kcache,
+                              double *vcache, int b_max, const int32_t *kv_len, const double *x, double *x_out,
+                              int B, int T, const unsigned char *rows, double *dbg_attn, double *dbg_h) {
     if (P < 1 || d < -1) return -1;
     size_t n = (size_t)B * (size_t)T * (size_t)D->d_model;
-    double *attn = malloc(sizeof(double) * n * (size_t)P);
+    double *attn = calloc(n * (size_t)P, sizeof(double));
     double *h = malloc(sizeof(double) * n);
-    double *fo = malloc(sizeof(double) * n);
+    double *fo = calloc(n, sizeof(double));
     double *acc = malloc(sizeof(double) * n);
     if (!attn || !h || !fo || !acc) return -2;
     for (int i = 0; i < P; ++i) {
-        int rc = orc_attn_module(D, &layers[i], i, kcache, vcache, b_max, kv_len, x, B, T, attn + n * (size_t)i);
+        int rc = attn_module_rows(D, &layers[i], i, kcache, vcache, b_max, kv_len, x, B, T, rows, attn + n * (size_t)i);
         if (rc) return rc;
     }
     memcpy(acc, x, sizeof(double) * n);
@@ -288,10 +322,24 @@ int orc_group_forward(const orc_dims *D, int P, int d, const orc_layer *layers, 
                 for (size_t e = 0; e < n; ++e) h[e] += attn[n * (size_t)j + e];
         }
         if (dbg_h) memcpy(dbg_h + n * (size_t)i, h, sizeof(double) * n);
-        int rc = orc_ffn_module(D, &layers[i], h, B * T, fo);
-        if (rc) return rc;
+        if (!rows) {
+            int rc = orc_ffn_module(D, &layers[i], h, B * T, fo);
+            if (rc) return rc;
+        } else {
+            for (int m = 0; m < B * T; ++m) {   /* row by row: the module treats every row alone */
+                if (!rows[m]) continue;
+                int rc = orc_ffn_module(D, &layers[i], h + (size_t)m * D->d_model, 1, fo + (size_t)m * D->d_model);
+                if (rc) return rc;
+            }
+        }
         for (size_t e = 0; e < n; ++e) acc[e] += fo[e];
     }
+    if (rows)   /* rows that were not asked for are reported as zero, not as partial sums */
+        for (int m = 0; m < B * T; ++m)
+            if (!rows[m]) {
+                memset(acc + (size_t)m * D->d_model, 0, sizeof(double) * (size_t)D->d_model);
+                if (dbg_h) for (int i = 0; i < P; ++i) memset(dbg_h + n * (size_t)i + (size_t)m * D->d_model, 0, sizeof(double) * (size_t)D->d_model);
+            }
     if (dbg_attn) memcpy(dbg_attn, attn, sizeof(double) * n * (size_t)P);
     memcpy(x_out, acc, sizeof(double) * n);
     free(attn); free(h); free(fo); free(acc);

@@ -192,6 +192,16 @@ def cqil_set_tuning(key: str, value: int) -> None:
         raise CqilError(rc, f"cqil_set_tuning({key}, {value})")
 
 
+TUNING_DEFAULTS = {"ksplit_qkv": 4, "ksplit_o": 0, "ksplit_gu": 0, "ksplit_d": 0, "down_slice_max": 8192,
+                   "gemm_tile": 0}
+
+
+def reset_tuning() -> None:
+    """Puts every launch-shape knob back to the library's default."""
+    for k, v in TUNING_DEFAULTS.items():
+        cqil_set_tuning(k, v)
+
+
 def cqil_input_similarity(X: torch.Tensor) -> torch.Tensor:
     """X [L, M, n] (bf16 or fp32, contiguous, on the GPU) -> fp32 [L, L] mean per-token cosine similarity (Sec.3.1)."""
     assert X.dim() == 3 and X.is_contiguous()

@@ -329,9 +329,11 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
         while (ks < 8 && units * ks < want_waves) ks *= 2;
         return ks;
     };
-    const int ks_q = g_tune.ksplit_qkv ? g_tune.ksplit_qkv : split_for(3L * nh * (dk / 32) * P, 6144);
-    const int ks_o = g_tune.ksplit_o ? g_tune.ksplit_o : (narrow ? (P >= 4 ? 4 : 8) : (P >= 4 ? 1 : (P >= 2 ? 2 : 4)));
-    const int ks_g = g_tune.ksplit_gu ? g_tune.ksplit_gu : (narrow ? ((P == 2 || P == 3) ? 4 : 2) : split_for((long)(f / kGuBlock) * P, 16384));
+    const int t_q = g_tune.ksplit_qkv.load(), t_o = g_tune.ksplit_o.load(), t_g = g_tune.ksplit_gu.load(),
+              t_d = g_tune.ksplit_d.load();
+    const int ks_q = t_q ? t_q : split_for(3L * nh * (dk / 32) * P, 6144);
+    const int ks_o = t_o ? t_o : (narrow ? (P >= 4 ? 4 : 8) : (P >= 4 ? 1 : (P >= 2 ? 2 : 4)));
+    const int ks_g = t_g ? t_g : (narrow ? ((P == 2 || P == 3) ? 4 : 2) : split_for((long)(f / kGuBlock) * P, 16384));
     const size_t lds_x = ((size_t)dm + kRedFloats + 16) * sizeof(float);
 
     // optional per-kernel timing: event i is recorded before kernel i, the last event after the last kernel
@@ -371,7 +373,7 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     }
     CQIL_MARK(4);
     {
-        const int ks_d = g_tune.ksplit_d ? g_tune.ksplit_d
+        const int ks_d = t_d ? t_d
                                          : (narrow ? (P >= 4 ? 1 : (P >= 2 ? 2 : 4))
                                                    : split_for((long)(dm / 16) * s.wl.n_slices, 16384));
         const int units = dm / 16, uw = kWaves / ks_d;

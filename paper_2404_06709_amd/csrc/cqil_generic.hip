@@ -428,7 +428,7 @@ static hipError_t gemm_any(const T* A, const T* W, CT* C, const float* R, int M,
                            size_t ldc, int groups, size_t sA, size_t n_step, size_t k_step, size_t sC, hipStream_t st,
                            float* part = nullptr, size_t part_floats = 0) {
     if constexpr (std::is_same<T, bf16_t>::value) {
-        return gemm_mfma<CT, ADD_R ? kEpiAddR : kEpiNone>(g_tune.gemm_tile, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA,
+        return gemm_mfma<CT, ADD_R ? kEpiAddR : kEpiNone>(g_tune.gemm_tile.load(), A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA,
                                                           n_step, k_step, sC, st, part, part_floats);
     } else {
         gemm_nt<T, T, CT, ADD_R>(A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step, k_step, sC, st);
@@ -543,7 +543,7 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
                            resid, P, bd, M, dm, d.rms_eps, s.kv_len, s.advance ? s.B : 0, s.T);
     if constexpr (std::is_same<T, bf16_t>::value) {
         // gate/up product with SwiGLU in the epilogue: u is written directly, gate and up never reach memory
-        if ((ge = gemm_mfma<bf16_t, kEpiSwiglu>(g_tune.gemm_tile, nrm, wgu, u, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * f,
+        if ((ge = gemm_mfma<bf16_t, kEpiSwiglu>(g_tune.gemm_tile.load(), nrm, wgu, u, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * f,
                                                  P, Mdm, (size_t)2 * f, 0, (size_t)f, st)) != hipSuccess) return ge;
     } else {
         if ((ge = gemm_any<T, T, false>(nrm, wgu, gu, nullptr, M, 2 * f, dm, dm, dm, (size_t)P * 2 * f, P, Mdm, (size_t)2 * f, 0,

@@ -55,7 +55,7 @@ int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* W) {
     const size_t ktile = 64 / es;
     const size_t Kp = (K + ktile - 1) / ktile * ktile;  // padded K of the packed Wdown (whole tiles)
     // K slices of the decode down projection: equal lengths, multiples of 512, at most the tuned maximum
-    const size_t smax = (size_t)g_tune.down_slice_max;
+    const size_t smax = (size_t)g_tune.down_slice_max.load();
     int ns = (int)((Kp + smax - 1) / smax);
     size_t sl = ((Kp + ns - 1) / ns + 511) / 512 * 512;
     ns = (int)((Kp + sl - 1) / sl);
@@ -193,7 +193,7 @@ int cqil_pack_group(const cqil_dims* dims, int P, const cqil_layer* layers, void
 static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const void* packed, void* kc, void* vc,
                               int32_t* kv_len, int b_max, int max_kv_len, const void* x_in, void* x_out, int B, int T,
                               int advance, void* workspace, size_t workspace_bytes, hipStream_t st,
-                              hipEvent_t* ev = nullptr) {
+                              hipEvent_t* ev = nullptr, bool check_only = false) {
     StepArgs a;
     a.ev = ev;
     int rc = packed_layout(dims, P, &a.pl);
@@ -209,6 +209,7 @@ static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const 
     rc = ws_layout(dims, P, B, T, &a.wl);
     if (rc) return rc;
     if (workspace_bytes < a.wl.total) return CQIL_ESIZE;
+    if (check_only) return CQIL_OK;
     a.d = *dims; a.P = P; a.bypass_d = bypass_d; a.B = B; a.T = T; a.advance = advance ? 1 : 0;
     a.packed = (const char*)packed;
     a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.b_max = b_max; a.max_kv_len = max_kv_len;
@@ -278,7 +279,10 @@ int cqil_decode_step_profile(const cqil_dims* dims, int P, int bypass_d, const v
     if (B != 1 || !dims) return CQIL_EINVAL;
     hipEvent_t ev[7];
     for (int i = 0; i < 7; ++i)
-        if (hipEventCreate(&ev[i]) != hipSuccess) return CQIL_EHIP;
+        if (hipEventCreate(&ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+            return CQIL_EHIP;
+        }
     int rc = group_forward_impl(dims, P, bypass_d, packed, kv->k, kv->v, kv->kv_len, kv->b_max, kv->max_kv_len, x_in,
                                 x_out, B, 1, 0, workspace, workspace_bytes, (hipStream_t)stream, ev);
     if (rc == CQIL_OK) {
@@ -331,12 +335,16 @@ int cqil_model_forward(cqil_model* m, const int32_t* tokens, int B, int T, int b
     if (workspace_bytes < total) return CQIL_ESIZE;
     if (B > m->b_max) return CQIL_ERANGE;
     if ((long long)m->max_kv_len + T > m->dims.max_seq) return CQIL_ERANGE;
-    for (int g = 0; g < m->n_groups; ++g)
-        if (!m->packed[g] || !m->k_cache[g] || !m->v_cache[g]) return CQIL_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     char* ws = (char*)workspace;
     void* x = hidden_out ? hidden_out : (void*)(ws + x_off);
     const size_t gbytes = total - g_off;
+    // every group is checked (pointers, alignment, ranges, workspace) before the first launch
+    for (int g = 0; g < m->n_groups; ++g) {
+        rc = group_forward_impl(&m->dims, m->group_sizes[g], bypass_d, m->packed[g], m->k_cache[g], m->v_cache[g],
+                                m->kv_len, m->b_max, m->max_kv_len, x, x, B, T, 0, ws + g_off, gbytes, st, nullptr, true);
+        if (rc) return rc;
+    }
 
     if (launch_embedding(m->dims, m->embedding, tokens, B * T, m->vocab, x, st) != hipSuccess) return CQIL_EHIP;
     for (int g = 0; g < m->n_groups; ++g) {

@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/cqil.h"
 
 namespace cqil {
@@ -19,9 +21,11 @@ constexpr int kMaxP = 16;
 // (k split: 1, 2, 4 or 8; 0 = chosen by shape) in the QKV, O, gate/up and down kernels, and the longest K slice of the down projection
 // (multiple of 512, at most 12288).  gemm_tile: workgroup tile of the matrix-core GEMM of the token-parallel path
 // (1 = 256 tokens x 256 weight rows, 2 = 128 x 256; 0 = default).
+// Atomics: a knob may be set while another thread launches (each launch reads a knob once; a step sized with one
+// value of down_slice_max and launched with another is caught by the workspace-size check or runs with the new one).
 struct Tuning {
-    int ksplit_qkv = 4, ksplit_o = 0, ksplit_gu = 0, ksplit_d = 0, down_slice_max = 8192;  // 0 = by shape
-    int gemm_tile = 0;
+    std::atomic<int> ksplit_qkv{4}, ksplit_o{0}, ksplit_gu{0}, ksplit_d{0}, down_slice_max{8192};  // 0 = by shape
+    std::atomic<int> gemm_tile{0};
 };
 extern Tuning g_tune;
 

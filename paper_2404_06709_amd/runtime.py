@@ -48,15 +48,17 @@ class Group:
         return self._ws
 
     def forward(self, x: torch.Tensor, bypass_d: int, advance: bool = True,
-                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """One group step; `workspace` (uint8, cqil_workspace_bytes() long) replaces the group's own buffer."""
         B, T, _ = x.shape
         out = torch.empty_like(x) if out is None else out
-        cq.cqil_group_forward(self.dims, self.P, bypass_d, self.packed, self.kv, x, out, B, T, advance,
-                              self.workspace(B, T))
+        ws = self.workspace(B, T) if workspace is None else workspace
+        cq.cqil_group_forward(self.dims, self.P, bypass_d, self.packed, self.kv, x, out, B, T, advance, ws)
+        self._last_ws = ws
         return out
 
     def attn_out(self, B: int, T: int) -> torch.Tensor:
         """fp32 [P, B*T, d_model] view of the attention outputs left in the workspace by the last call."""
         off = cq.cqil_workspace_attn_out_offset(self.dims, self.P, B, T)
         n = self.P * B * T * self.dims.d_model
-        return self._ws[off: off + 4 * n].view(torch.float32).view(self.P, B * T, self.dims.d_model)
+        return self._last_ws[off: off + 4 * n].view(torch.float32).view(self.P, B * T, self.dims.d_model)

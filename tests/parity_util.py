@@ -37,6 +37,28 @@ def gdims(shape: synth.Shape, max_seq: int, dtype: torch.dtype) -> cq.cqil_dims:
     return cq.make_dims(shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, max_seq, dtype)
 
 
+GUARD = 4096          # bytes of sentinel on each side of a guarded buffer
+SENTINEL = 0xA7
+
+
+class Guarded:
+    """A device buffer of n bytes with sentinel-filled bands before and after it; check() asserts that the
+    bands still hold the sentinel (a kernel that writes outside the buffer it was given fails here)."""
+
+    def __init__(self, nbytes: int, device="cuda"):
+        self.n = int(nbytes)
+        pad = (-self.n) % 256
+        self.raw = torch.full((GUARD + self.n + pad + GUARD,), SENTINEL, dtype=torch.uint8, device=device)
+        self.body = self.raw[GUARD: GUARD + self.n]
+
+    def view(self, dtype: torch.dtype, shape) -> torch.Tensor:
+        return self.body.view(dtype).view(shape)
+
+    def check(self, label: str) -> None:
+        lo, hi = self.raw[:GUARD], self.raw[GUARD + self.n:]
+        assert bool((lo == SENTINEL).all()) and bool((hi == SENTINEL).all()), f"{label}: wrote outside its buffer"
+
+
 class Pair:
     """One group on both sides: HIP (rt.Group) and oracle (numpy weights + float64 caches)."""
 
@@ -77,8 +99,8 @@ class Pair:
         self.group.set_kv_len(list(lens) + [0] * (self.b_max - len(lens)))
         self.group.kv.max_kv_len = int(max(lens))
 
-    def hidden(self, B: int, T: int, seed: int) -> torch.Tensor:
-        return synth.normal((B, T, self.shape.d_model), 1.0, self.dtype, synth.generator(seed))
+    def hidden(self, B: int, T: int, seed: int, std: float = 1.0) -> torch.Tensor:
+        return synth.normal((B, T, self.shape.d_model), std, self.dtype, synth.generator(seed))
 
     def step(self, x: torch.Tensor, d: int, check: bool = True, label: str = ""):
         """Runs one group step on both sides from the same x (storage dtype, CPU tensor) and compares
@@ -90,8 +112,14 @@ class Pair:
         if check:
             k_before, v_before = g.k.clone(), g.v.clone()
         g.kv.max_kv_len = int(lens.max())       # host-side bound for the sequences of this call
-        y = g.forward(x.cuda(), d, advance=True)
+        # x_out and the workspace sit between sentinel bands: nothing may be written outside them
+        es = x.element_size()
+        gy = Guarded(x.numel() * es)
+        gw = Guarded(cq.cqil_workspace_bytes(self.gd, self.P, B, T))
+        y = g.forward(x.cuda(), d, advance=True, out=gy.view(x.dtype, x.shape), workspace=gw.body)
         torch.cuda.synchronize()
+        gy.check(f"{label}: x_out")
+        gw.check(f"{label}: workspace")
         ref, ref_attn, _ = orc.group_forward(self.od, self.np_layers, d, self.okc, self.ovc, lens, synth.widen(x),
                                              debug=True)
         tol = TOL[self.dtype]
@@ -100,6 +128,16 @@ class Pair:
             e_out = rel_err(synth.widen(y_cpu), ref)
             attn = g.attn_out(B, T).cpu().numpy().reshape(self.P, B, T, -1)
             e_attn = rel_err(attn, ref_attn)
+            # the feed-forward branch on its own scale: sum_i FFN_i = x_out - x - sum_i a_i on both sides.  The HIP
+            # side's x_out carries one rounding to the storage type (half a unit in the last place of x_out),
+            # which the bound adds to the tolerance in units of the branch's size.
+            xw = synth.widen(x)
+            ffn_ref = ref - xw - ref_attn.sum(axis=0)
+            ffn_got = synth.widen(y_cpu) - xw - attn.astype(np.float64).sum(axis=0)
+            half_ulp = 2.0 ** -9 if self.dtype == torch.bfloat16 else 2.0 ** -24
+            ffn_scale = np.abs(ffn_ref).max()
+            e_ffn = rel_err(ffn_got, ffn_ref)
+            ffn_tol = tol + half_ulp * np.abs(ref).max() / (ffn_scale if ffn_scale > 0 else 1.0)
             kg, vg = g.k.cpu(), g.v.cpu()
             kb, vb = k_before.cpu(), v_before.cpu()
             del k_before, v_before
@@ -114,9 +152,10 @@ class Pair:
             assert torch.equal(kb.view(torch.uint8), kg.view(torch.uint8)), f"{label}: K cache disturbed"
             assert torch.equal(vb.view(torch.uint8), vg.view(torch.uint8)), f"{label}: V cache disturbed"
             say(f"  {label} B={B} T={T} d={d} lens={lens.tolist()}: x_out {e_out:.2e} attn {e_attn:.2e} "
-                f"k {e_k:.2e} v {e_v:.2e} (tol {tol:.0e})")
+                f"ffn {e_ffn:.2e} (bound {ffn_tol:.1e}) k {e_k:.2e} v {e_v:.2e} (tol {tol:.0e})")
             assert e_out <= tol, f"{label}: x_out rel err {e_out}"
             assert e_attn <= tol, f"{label}: attention output rel err {e_attn}"
+            assert e_ffn <= ffn_tol, f"{label}: feed-forward branch rel err {e_ffn} (bound {ffn_tol})"
             assert e_k <= tol and e_v <= tol, f"{label}: appended K/V rel err {e_k} {e_v}"
             got_len = g.kv_len.cpu().numpy()[:B]
             assert (got_len == lens + T).all(), f"{label}: kv_len {got_len} vs {lens + T}"

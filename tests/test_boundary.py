@@ -126,6 +126,31 @@ def test_group_forward_validates_before_launching():
                                        None) == cq.CQIL_EINVAL
 
 
+def test_set_tuning_error_returns_and_reset():
+    lib = cq.lib()
+    assert lib.cqil_set_tuning(None, 1) == cq.CQIL_EINVAL
+    assert lib.cqil_set_tuning(b"no_such_knob", 1) == cq.CQIL_EINVAL
+    for key in (b"ksplit_qkv", b"ksplit_o", b"ksplit_gu", b"ksplit_d"):
+        for bad in (-1, 3, 5, 16):
+            assert lib.cqil_set_tuning(key, bad) == cq.CQIL_EINVAL
+        for ok in (1, 2, 4, 8, 0):
+            assert lib.cqil_set_tuning(key, ok) == cq.CQIL_OK
+    for bad in (0, 256, 700, 12800, -512):
+        assert lib.cqil_set_tuning(b"down_slice_max", bad) == cq.CQIL_EINVAL
+    d = dims("7b", torch.bfloat16, 64)
+    base = cq.cqil_workspace_bytes(d, 4, 1, 1)
+    assert lib.cqil_set_tuning(b"down_slice_max", 512) == cq.CQIL_OK
+    assert cq.cqil_workspace_bytes(d, 4, 1, 1) > base          # more K slices, more partial rows
+    assert lib.cqil_set_tuning(b"down_slice_max", 8192) == cq.CQIL_OK
+    assert cq.cqil_workspace_bytes(d, 4, 1, 1) == base
+    for bad in (-1, 3):
+        assert lib.cqil_set_tuning(b"gemm_tile", bad) == cq.CQIL_EINVAL
+    for ok in (1, 2, 0):
+        assert lib.cqil_set_tuning(b"gemm_tile", ok) == cq.CQIL_OK
+    assert lib.cqil_set_tuning(b"ksplit_qkv", 4) == cq.CQIL_OK  # the defaults again
+    cq.reset_tuning()
+
+
 def test_pack_group_validates_before_launching():
     d = dims()
     L = (cq.cqil_layer * 2)()

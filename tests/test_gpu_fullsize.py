@@ -52,6 +52,50 @@ def test_wide_batch_llama13b_group_P4_batch40():
     pair.step(pair.hidden(B, 1, seed=31), 1, label="13b batch 40")
 
 
+@pytest.mark.parametrize("B", [128, 256])
+def test_batch_sweep_llama13b_group_P4_wide_batches_sampled(B):
+    """The wide end of the batch sweep at full 13B width: B = 128 and 256 sequences (several 128-token tiles, the
+    four-wave one-query attention), ragged caches of 64..330 tokens, one new token each.  The oracle runs the
+    sampled sequences one by one (a sequence's output depends on no other sequence)."""
+    shape, P, max_seq = synth.SHAPES["13b"], 4, 336
+    lens = synth.kv_lengths(B, 64, 330, seed=1100 + B)
+    gd, od = gdims(shape, max_seq, BF16), odims(shape, max_seq, BF16)
+    layers = synth.make_layers(P, shape, BF16, seed=1013, device="cuda")
+    nl = [synth.layer_to_numpy(L) for L in layers]
+    group = rt.Group(gd, layers, b_max=B)
+    torch.cuda.synchronize()
+    del layers
+    gen = synth.generator(2100 + B, "cuda")
+    group.k.copy_(synth.normal(tuple(group.k.shape), 1.0, BF16, gen))
+    group.v.copy_(synth.normal(tuple(group.v.shape), 1.0, BF16, gen))
+    k0, v0 = group.k.clone(), group.v.clone()
+    group.set_kv_len(lens.tolist())
+    x = synth.normal((B, 1, shape.d_model), 1.0, BF16, gen)
+    y = group.forward(x, 1, advance=True)
+    torch.cuda.synchronize()
+    attn = group.attn_out(B, 1).view(P, B, shape.d_model)
+    assert group.kv_len.cpu().tolist() == (lens + 1).tolist()
+    sample = sorted({0, 1, 31, 127, B - 129 if B > 129 else 64, B - 1, int(np.argmax(lens)), int(np.argmin(lens))})
+    worst = 0.0
+    for b in sample:
+        S = int(lens[b])
+        okc, ovc = orc.new_cache(P, 1, od), orc.new_cache(P, 1, od)
+        okc[:, 0, :, :S] = synth.widen(k0[:, b, :, :S]); ovc[:, 0, :, :S] = synth.widen(v0[:, b, :, :S])
+        ref, ref_attn, _ = orc.group_forward(od, nl, 1, okc, ovc, [S], synth.widen(x[b:b + 1]), debug=True)
+        e = (rel_err(synth.widen(y[b]), ref[0]), rel_err(attn[:, b].cpu().numpy(), ref_attn[:, 0, 0]),
+             rel_err(synth.widen(group.k[:, b, :, S]), okc[:, 0, :, S]), rel_err(synth.widen(group.v[:, b, :, S]), ovc[:, 0, :, S]))
+        say(f"  B={B} sequence {b} (cache {S}): x_out {e[0]:.2e} attn {e[1]:.2e} k {e[2]:.2e} v {e[3]:.2e}")
+        worst = max(worst, *e)
+    assert worst <= TOL[BF16]
+    # every slot but the appended one of every sequence is untouched
+    idx = torch.from_numpy(lens.astype(np.int64)).cuda()
+    for cache, before in ((group.k, k0), (group.v, v0)):
+        changed = (cache != before).any(dim=-1).any(dim=0).any(dim=1)          # [B, max_seq]
+        only = torch.zeros_like(changed)
+        only[torch.arange(B, device="cuda"), idx] = True
+        assert not (changed & ~only).any()
+
+
 def test_config4_llama13b_prefill_P2_4x2048_sampled():
     """13B-shaped prefill, P=2, batch 4 x 2048 tokens, causal, empty caches, at full size on the GPU.
     The oracle computes the first 20 positions of two of the sequences (a causal prefix does not depend on
@@ -75,6 +119,20 @@ def test_config4_llama13b_prefill_P2_4x2048_sampled():
         e_v = rel_err(synth.widen(g.v[:, b, :, :NPRE]), ovc[:, 0, :, :NPRE])
         say(f"  cfg4 sequence {b}, first {NPRE} positions: x_out {e_out:.2e} attn {e_attn:.2e} k {e_k:.2e} v {e_v:.2e}")
         assert max(e_out, e_attn, e_k, e_v) <= TOL[BF16]
+    # rows deep inside the chunk (query blocks 1, 7 and the last; later waves of a block; the very last position):
+    # the oracle computes the keys and values of the whole sequence and the outputs of the sampled rows only
+    b, sample = 1, [130, 131, 1000, 1917, 2047]
+    rows = np.zeros((1, T), dtype=bool)
+    rows[0, sample] = True
+    okc, ovc = orc.new_cache(P, 1, pair.od), orc.new_cache(P, 1, pair.od)
+    ref, ref_attn, _ = orc.group_forward_rows(pair.od, pair.np_layers, 1, okc, ovc, [0], synth.widen(x[b:b + 1]), rows)
+    e_out = rel_err(synth.widen(y[b, sample]), ref[0, sample])
+    e_attn = rel_err(attn[:, b, sample].cpu().numpy(), ref_attn[:, 0, sample])
+    e_k = rel_err(synth.widen(g.k[:, b]), okc[:, 0])
+    e_v = rel_err(synth.widen(g.v[:, b]), ovc[:, 0])
+    say(f"  cfg4 sequence {b}, rows {sample}: x_out {e_out:.2e} attn {e_attn:.2e}; all {T} keys {e_k:.2e} values {e_v:.2e}")
+    assert max(e_out, e_attn, e_k, e_v) <= TOL[BF16]
+    del okc, ovc
     # any-size property on the GPU: same prefill minus the last token, then one decode step per sequence
     k_full, v_full = g.k.clone(), g.v.clone()
     y_last = y[:, T - 1:].clone()
@@ -130,7 +188,7 @@ def test_config5_llama33b_shape_reduced_depth_model():
         e_l = rel_err(logits.cpu().numpy(), ref["logits"])
         same = int(nxt.cpu()[0].item() == ref["next"][0])
         say(f"  cfg5 reduced depth, step {step} (T={T}): hidden {e_h:.2e} logits {e_l:.2e} argmax agrees: {same}")
-        assert e_h <= 3 * TOL[BF16] and e_l <= 3 * TOL[BF16]     # three group steps in a row
+        assert e_h <= TOL[BF16] and e_l <= TOL[BF16]
         tokens = torch.from_numpy(ref["next"].reshape(1, 1).astype(np.int32))
 
 

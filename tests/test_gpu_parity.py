@@ -7,7 +7,7 @@ import oracle as orc
 from paper_2404_06709_amd import binding as cq
 from paper_2404_06709_amd import runtime as rt
 from paper_2404_06709_amd import synth
-from parity_util import TOL, Pair, gdims, odims, rel_err, say
+from parity_util import TOL, Guarded, Pair, gdims, odims, rel_err, say
 
 pytestmark = pytest.mark.gpu
 
@@ -302,7 +302,76 @@ def test_group_steps_replay_from_a_hip_graph(dtype):
         assert torch.equal(g.k, k_e) and g.kv_len.cpu()[0].item() == S0 + 7
 
 
+# ------------------------------------------------------------------------------------------ launch-shape knobs
+KNOBS = [("ksplit_qkv", 1), ("ksplit_qkv", 2), ("ksplit_qkv", 8), ("ksplit_o", 1), ("ksplit_o", 2), ("ksplit_o", 4),
+         ("ksplit_o", 8), ("ksplit_gu", 1), ("ksplit_gu", 2), ("ksplit_gu", 4), ("ksplit_gu", 8), ("ksplit_d", 1),
+         ("ksplit_d", 2), ("ksplit_d", 4), ("ksplit_d", 8), ("down_slice_max", 512), ("down_slice_max", 2048),
+         ("down_slice_max", 12288)]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_every_decode_launch_shape_knob_matches_oracle(dtype):
+    """cqil_set_tuning selects other k splits of the four single-token projections and other K-slice lengths of the
+    down projection: every value that changes a launch is run against the oracle (WIDE at P = 4 has a
+    concatenated K of 11008: 22, 6 and 1 slices), with the knobs put back afterwards."""
+    try:
+        for shape, P in ((WIDE, 4), (MID, 1)):
+            pair = Pair(shape, P, dtype, max_seq=160, b_max=1, seed=3100 + P, w_std=0.05, gain_jitter=0.1)
+            pair.fill_cache([130], seed=21)
+            for i, (key, val) in enumerate(KNOBS):
+                cq.reset_tuning()
+                cq.cqil_set_tuning(key, val)
+                pair.set_lens([130])
+                pair.step(pair.hidden(1, 1, seed=40 + i), 1, label=f"{key}={val} P={P} {dtype}")
+    finally:
+        cq.reset_tuning()
+
+
+@pytest.mark.parametrize("tile", [1, 2])
+def test_gemm_tile_knob_matches_oracle(tile):
+    """gemm_tile 1 = the 8-wave 256 x 256 instantiation of the matrix-core GEMM (M > 32 rows), 2 = the tiled
+    kernel also for up to 8 rows (where the default is the barrier-free streaming kernel)."""
+    try:
+        cq.cqil_set_tuning("gemm_tile", tile)
+        pair = Pair(MID, 2, torch.bfloat16, max_seq=400, b_max=8, seed=3200 + tile, w_std=0.05, gain_jitter=0.1)
+        pair.fill_cache([0, 70, 3, 128, 9, 31, 200, 64], seed=22)
+        pair.step(pair.hidden(2, 150, seed=1), 1, label=f"gemm_tile={tile} 300 rows")     # ragged second tile
+        pair.step(pair.hidden(8, 1, seed=2), 1, label=f"gemm_tile={tile} 8 rows")
+        pair.step(pair.hidden(3, 1, seed=3), 0, label=f"gemm_tile={tile} 3 rows")
+        pair.step(pair.hidden(1, 40, seed=4), 1, label=f"gemm_tile={tile} 40 rows")
+    finally:
+        cq.reset_tuning()
+
+
+# ------------------------------------------------------------------------------------------ branch-dominated inputs
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape,P", [(TINY, 2), (MID, 4)])
+def test_small_hidden_states_let_the_branches_dominate(shape, P, dtype):
+    """Hidden states N(0, 0.05): RMSNorm makes the attention and feed-forward branches independent of the
+    input's scale, so they are 10-20 times larger than x here and an error of either branch shows in x_out at
+    full size (with x ~ N(0,1) it would hide behind x)."""
+    pair = Pair(shape, P, dtype, max_seq=200, b_max=12, seed=3300 + P, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([9, 0, 130, 4, 77, 1, 33, 64, 12, 100, 2, 50], seed=23)
+    for (B, T, d, seed) in ((1, 1, 1, 1), (3, 5, 1, 2), (12, 1, 0, 3), (1, 1, P - 1, 4), (2, 40, 1, 5)):
+        x = pair.hidden(B, T, seed=seed, std=0.05)
+        y, ref = pair.step(x, d, label=f"small x {dtype} P={P}")
+        assert np.abs(ref - synth.widen(x)).max() > 5 * np.abs(synth.widen(x)).max()
+
+
 # ------------------------------------------------------------------------------------------ prefill / batch
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [MID, ODD])
+def test_prefill_over_several_query_blocks_and_ragged_caches(shape, dtype):
+    """Chunks of 300 tokens onto caches of 0 and 70 tokens: three 128-query blocks per head (the last ragged),
+    waves whose first query lies beyond several unmasked key tiles, the longest-first block order, and a
+    non-empty cache under several query blocks; head sizes 128 (MID) and 64 (ODD).  Every position is compared."""
+    pair = Pair(shape, 2, dtype, max_seq=400, b_max=2, seed=3400, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([0, 70], seed=24)
+    pair.step(pair.hidden(2, 300, seed=1), 1, label=f"prefill 2 x 300 {dtype}")
+    pair.set_lens([0, 70])
+    pair.step(pair.hidden(1, 257, seed=2), 0, label=f"prefill 1 x 257 {dtype}")   # one query past two blocks
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("shape", [TINY, ODD])
 def test_token_parallel_path_matches_oracle(shape, dtype):
@@ -433,10 +502,14 @@ def test_model_forward_teacher_forced(dtype):
     agree = 0
     for step in range(9):
         T = tokens.shape[1]
-        ws = torch.empty(cq.cqil_model_workspace_bytes(model, 1, T), dtype=torch.uint8, device="cuda")
-        logits = torch.empty(1, vocab, dtype=torch.float32, device="cuda")
-        nxt = torch.empty(1, dtype=torch.int32, device="cuda")
-        hid = torch.empty(1, T, TINY.d_model, dtype=dtype, device="cuda")
+        # every output and the workspace between sentinel bands
+        gws = Guarded(cq.cqil_model_workspace_bytes(model, 1, T))
+        glog, gnxt = Guarded(vocab * 4), Guarded(16)
+        ghid = Guarded(T * TINY.d_model * (4 if dtype == torch.float32 else 2))
+        ws = gws.body
+        logits = glog.view(torch.float32, (1, vocab))
+        nxt = gnxt.body[:4].view(torch.int32)
+        hid = ghid.view(dtype, (1, T, TINY.d_model))
         cq.cqil_model_forward(model, tokens.cuda(), 1, T, 1, True, hid, logits, nxt, ws)
         torch.cuda.synchronize()
         ref = orc.model_forward(od, nl, sizes, 1, emb, gfin, head, okc, ovc, [olen], tokens.numpy())
@@ -444,8 +517,9 @@ def test_model_forward_teacher_forced(dtype):
         e_h = rel_err(synth.widen(hid.cpu()), ref["hidden"])
         e_l = rel_err(logits.cpu().numpy(), ref["logits"])
         say(f"  model {dtype} step {step}: hidden {e_h:.2e} logits {e_l:.2e}")
-        # six layers in a row: the per-group tolerance compounds, allow the sum over group steps
-        assert e_h <= 4 * TOL[dtype] and e_l <= 4 * TOL[dtype]
+        assert e_h <= TOL[dtype] and e_l <= TOL[dtype]
+        glog.check(f"model {dtype} step {step}: logits"); gnxt.check(f"model {dtype} step {step}: next token")
+        ghid.check(f"model {dtype} step {step}: hidden state"); gws.check(f"model {dtype} step {step}: workspace")
         top2 = np.sort(ref["logits"][0])[-2:]
         if top2[1] - top2[0] > 8 * TOL[dtype] * np.abs(ref["logits"]).max():
             assert nxt.cpu()[0].item() == ref["next"][0]
@@ -479,7 +553,7 @@ def test_model_forward_general_partitions(L, p, s, e):
         e_h = rel_err(synth.widen(hid.cpu()), ref["hidden"])
         e_l = rel_err(logits.cpu().numpy(), ref["logits"])
         say(f"  partition {sizes} step {step}: hidden {e_h:.2e} logits {e_l:.2e}")
-        assert e_h <= 4 * TOL[dtype] and e_l <= 4 * TOL[dtype]
+        assert e_h <= TOL[dtype] and e_l <= TOL[dtype]
         tokens = torch.from_numpy(ref["next"].reshape(1, 1).astype(np.int32))
 
 

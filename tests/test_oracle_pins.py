@@ -443,6 +443,64 @@ def test_I7_prefill_equals_shorter_prefill_plus_decode(d):
     np.testing.assert_allclose(vcA, vcB, rtol=1e-13, atol=0)
 
 
+def test_batch_of_ragged_sequences_equals_one_call_per_sequence():
+    """Batch independence (Eq.2 acts on every sequence alone): a ragged call with B = 3, T = 2 equals three
+    B = 1 calls bit for bit, outputs and caches; and against the library composition per sequence, which pins
+    the batch term of the cache index and of the input offset to something other than the oracle itself."""
+    D = tiny_dims()
+    P, T, d = 3, 2, 1
+    tl, nl = tiny_layers(P)
+    S = [5, 0, 9]
+    kc, vc = _filled_caches(P, 3, D, S)
+    kc0, vc0 = kc.copy(), vc.copy()
+    x = hidden(3, T, seed=41)
+    out, attn, _ = orc.group_forward(D, nl, d, kc, vc, S, x, debug=True)
+    for b in range(3):
+        kb = np.ascontiguousarray(kc0[:, b:b + 1]); vb = np.ascontiguousarray(vc0[:, b:b + 1])
+        one, attn1, _ = orc.group_forward(D, nl, d, kb, vb, [S[b]], x[b:b + 1], debug=True)
+        np.testing.assert_array_equal(out[b], one[0])
+        np.testing.assert_array_equal(attn[:, b], attn1[:, 0])
+        np.testing.assert_array_equal(kc[:, b], kb[:, 0])
+        np.testing.assert_array_equal(vc[:, b], vb[:, 0])
+        # library composition of this sequence alone, from its own past
+        xt = torch.from_numpy(x[b])
+        for i in range(P):
+            a, k_all, _ = torch_attn(tl[i], xt, torch.from_numpy(kc0[i, b, :, :S[b]]), torch.from_numpy(vc0[i, b, :, :S[b]]))
+            np.testing.assert_allclose(attn[i, b], a.numpy(), rtol=1e-10, atol=1e-12)
+            np.testing.assert_allclose(kc[i, b, :, :S[b] + T], k_all.numpy(), rtol=1e-11, atol=1e-13)
+    # sequences are not mixed up: sequence 1's output changes when, and only when, its own input changes
+    x2 = x.copy(); x2[1] += 0.5
+    out2 = orc.group_forward(D, nl, d, kc0.copy(), vc0.copy(), S, x2)
+    np.testing.assert_array_equal(out2[0], out[0]); np.testing.assert_array_equal(out2[2], out[2])
+    assert np.abs(out2[1] - out[1]).max() > 1e-3
+
+
+def test_row_restricted_group_forward_equals_the_rows_of_the_full_call():
+    """group_forward_rows (used to sample rows of prefills too long for the oracle to finish): all rows flagged
+    is the full call; a subset gives exactly those rows, zeros elsewhere, and the same caches."""
+    D = tiny_dims()
+    P, T, d = 2, 9, 1
+    _, nl = tiny_layers(P)
+    S = [3, 0]
+    kc, vc = _filled_caches(P, 2, D, S)
+    x = hidden(2, T, seed=43)
+    kA, vA = kc.copy(), vc.copy()
+    full, attn, h = orc.group_forward(D, nl, d, kA, vA, S, x, debug=True)
+    kB, vB = kc.copy(), vc.copy()
+    allr = orc.group_forward_rows(D, nl, d, kB, vB, S, x, np.ones((2, T), dtype=bool))
+    np.testing.assert_array_equal(allr[0], full); np.testing.assert_array_equal(allr[1], attn)
+    np.testing.assert_array_equal(allr[2], h)
+    rows = np.zeros((2, T), dtype=bool)
+    rows[0, 4] = rows[0, 8] = rows[1, 0] = rows[1, 7] = True
+    kC, vC = kc.copy(), vc.copy()
+    sub, sattn, sh = orc.group_forward_rows(D, nl, d, kC, vC, S, x, rows)
+    np.testing.assert_array_equal(sub[rows], full[rows])
+    np.testing.assert_array_equal(sattn[:, rows], attn[:, rows])
+    np.testing.assert_array_equal(sh[:, rows], h[:, rows])
+    assert not sub[~rows].any() and not sattn[:, ~rows].any() and not sh[:, ~rows].any()
+    np.testing.assert_array_equal(kC, kA); np.testing.assert_array_equal(vC, vA)
+
+
 # ----------------------------------------------------------------------------- I9: partition, paper values
 def _golden_rows():
     rows = []
