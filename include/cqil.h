@@ -155,6 +155,19 @@ int cqil_group_forward(const cqil_dims *dims, int P, int bypass_d, const void *p
                        const void *x_in, void *x_out, int B, int T, int advance_kv_len, void *workspace,
                        size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): cqil_group_forward with the workspace in a static device array
+ * of cqil_static_scratch_bytes() bytes (4 MiB) that is part of the library's code object; every GPU the library
+ * runs on holds its own copy until the process ends.  Same arguments, results and error returns as
+ * cqil_group_forward, bit for bit (the same kernels run); a step whose cqil_workspace_bytes() exceeds the array
+ * (long prefill chunks, wide batches) is CQIL_ESIZE.  Single-token decode of a 33B-shaped group of up to 16 layers
+ * fits.  The call allocates nothing, frees nothing and does not synchronise; its first call on a device looks up
+ * the array's address (CQIL_EHIP if that fails).  All calls on one GPU share that GPU's array: calls that may
+ * overlap in time on one GPU (different streams, different threads) race; serialise them on one stream. */
+size_t cqil_static_scratch_bytes(void);
+int cqil_group_forward_static(const cqil_dims *dims, int P, int bypass_d, const void *packed, cqil_kv *kv /* host */,
+                              const void *x_in, void *x_out, int B, int T, int advance_kv_len, void *stream);
+
 /* Measurement aid for a single-token decode step (B must be 1, T == 1, kv_len not advanced): the same six
  * kernels as cqil_group_forward, with HIP events recorded on `stream` around each of them.  Waits for the
  * step to finish and writes the six elapsed times in milliseconds to kernel_ms_out (host, 6 floats), in

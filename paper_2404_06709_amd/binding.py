@@ -80,6 +80,10 @@ def lib() -> C.CDLL:
         L.cqil_group_forward.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_void_p, C.POINTER(cqil_kv),
                                          C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
+        L.cqil_static_scratch_bytes.restype = C.c_size_t
+        L.cqil_static_scratch_bytes.argtypes = []
+        L.cqil_group_forward_static.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_void_p, C.POINTER(cqil_kv),
+                                                C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.cqil_decode_step_profile.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_void_p, C.POINTER(cqil_kv),
                                                C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p,
                                                C.POINTER(C.c_float)]
@@ -184,6 +188,19 @@ def cqil_group_forward(dims: cqil_dims, P: int, bypass_d: int, packed: torch.Ten
                                   workspace.numel() * workspace.element_size(), _stream())
     if rc:
         raise CqilError(rc, "cqil_group_forward")
+
+
+def cqil_static_scratch_bytes() -> int:
+    return int(lib().cqil_static_scratch_bytes())
+
+
+def cqil_group_forward_static(dims: cqil_dims, P: int, bypass_d: int, packed: torch.Tensor, kv: cqil_kv,
+                              x_in: torch.Tensor, x_out: torch.Tensor, B: int, T: int, advance_kv_len: bool) -> None:
+    """cqil_group_forward with the library's static scratch array as the workspace (allocates nothing)."""
+    rc = lib().cqil_group_forward_static(C.byref(dims), P, bypass_d, _ptr(packed), C.byref(kv), _ptr(x_in), _ptr(x_out),
+                                         B, T, 1 if advance_kv_len else 0, _stream())
+    if rc:
+        raise CqilError(rc, "cqil_group_forward_static")
 
 
 def cqil_set_tuning(key: str, value: int) -> None:

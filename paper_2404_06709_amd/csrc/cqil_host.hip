@@ -2,6 +2,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "cqil_internal.h"
 
 namespace cqil {
@@ -89,6 +91,29 @@ int ws_layout(const cqil_dims* d, int P, int B, int T, WsLayout* W) {
 }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+// Workspace of cqil_group_forward_static: one array per GPU, part of the loaded code object, held until the process
+// ends.  Host code never passes the array's name to a kernel (on the host the name is only a handle of the symbol):
+// the device address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices];
+
+// device address of this GPU's copy of `scratch` (looked up on the first call with that device current)
+static int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CQIL_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CQIL_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CQIL_OK;
+}
 
 }  // namespace cqil
 
@@ -267,6 +292,28 @@ int cqil_group_forward(const cqil_dims* dims, int P, int bypass_d, const void* p
     if (!kv) return CQIL_EINVAL;
     int rc = group_forward_impl(dims, P, bypass_d, packed, kv->k, kv->v, kv->kv_len, kv->b_max, kv->max_kv_len, x_in,
                                 x_out, B, T, advance_kv_len, workspace, workspace_bytes, (hipStream_t)stream);
+    if (rc == CQIL_OK && advance_kv_len) kv->max_kv_len += T;
+    return rc;
+}
+
+size_t cqil_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int cqil_group_forward_static(const cqil_dims* dims, int P, int bypass_d, const void* packed, cqil_kv* kv,
+                              const void* x_in, void* x_out, int B, int T, int advance_kv_len, void* stream) {
+    if (!kv) return CQIL_EINVAL;
+    WsLayout W;
+    int rc = ws_layout(dims, P, B, T, &W);
+    if (rc) return rc;
+    if (W.total > kStaticScratchBytes) return CQIL_ESIZE;  // the step needs more scratch than the static array holds
+    // every argument is checked before the first HIP call (a stand-in address takes the workspace's place)
+    rc = group_forward_impl(dims, P, bypass_d, packed, kv->k, kv->v, kv->kv_len, kv->b_max, kv->max_kv_len, x_in, x_out,
+                            B, T, advance_kv_len, (void*)kAlign, kStaticScratchBytes, (hipStream_t)stream, nullptr, true);
+    if (rc) return rc;
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws)) != CQIL_OK) return rc;
+    // nothing in the workspace has to start at zero: every kernel writes what a later one reads
+    rc = group_forward_impl(dims, P, bypass_d, packed, kv->k, kv->v, kv->kv_len, kv->b_max, kv->max_kv_len, x_in, x_out,
+                            B, T, advance_kv_len, ws, kStaticScratchBytes, (hipStream_t)stream);
     if (rc == CQIL_OK && advance_kv_len) kv->max_kv_len += T;
     return rc;
 }

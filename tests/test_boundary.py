@@ -126,6 +126,35 @@ def test_group_forward_validates_before_launching():
                                        None) == cq.CQIL_EINVAL
 
 
+def test_static_scratch_entry_point_validates_before_any_gpu_call():
+    """The no-allocation variant checks every argument on the host first (no GPU in this container: a call that
+    got as far as asking HIP for the array's address would return CQIL_EHIP, not these codes)."""
+    d = dims(max_seq=64)
+    lib = cq.lib()
+    assert lib.cqil_static_scratch_bytes() == 4 << 20
+
+    def call(P=2, bypass=1, packed=0x1000, x=0x1000, y=0x1000, B=1, T=1, b_max=1, max_kv=0, kvp=True):
+        kv = cq.cqil_kv(0x1000, 0x1000, 0x1000, b_max, max_kv)
+        return lib.cqil_group_forward_static(C.byref(d), P, bypass, packed, C.byref(kv) if kvp else None, x, y, B, T, 0,
+                                             None)
+
+    assert call(kvp=False) == cq.CQIL_EINVAL
+    assert call(P=0) == cq.CQIL_EINVAL
+    assert call(bypass=-2) == cq.CQIL_EINVAL
+    assert call(packed=None) == cq.CQIL_EINVAL
+    assert call(x=0x1004) == cq.CQIL_EINVAL
+    assert call(B=2) == cq.CQIL_ERANGE
+    assert call(max_kv=64) == cq.CQIL_ERANGE
+    # a step whose workspace exceeds the static array is refused with the size error
+    big = dims("13b", torch.bfloat16, 4096)
+    assert cq.cqil_workspace_bytes(big, 2, 4, 2048) > lib.cqil_static_scratch_bytes()
+    kv = cq.cqil_kv(0x1000, 0x1000, 0x1000, 4, 0)
+    assert lib.cqil_group_forward_static(C.byref(big), 2, 1, 0x1000, C.byref(kv), 0x1000, 0x1000, 4, 2048, 0,
+                                         None) == cq.CQIL_ESIZE
+    # single-token decode of a 33B-shaped group of 16 layers fits
+    assert 0 < cq.cqil_workspace_bytes(dims("33b", torch.bfloat16, 2048), 16, 1, 1) <= lib.cqil_static_scratch_bytes()
+
+
 def test_set_tuning_error_returns_and_reset():
     lib = cq.lib()
     assert lib.cqil_set_tuning(None, 1) == cq.CQIL_EINVAL
