@@ -177,6 +177,12 @@ int cqil_decode_step_profile(const cqil_dims *dims, int P, int bypass_d, const v
                              const void *x_in, void *x_out, int B, void *workspace, size_t workspace_bytes,
                              void *stream, float *kernel_ms_out /* host */);
 
+/* Measurement aid: one kernel that reads buf[0 .. bytes) (bytes a multiple of 16, buf 16-byte aligned) exactly once
+ * with the streaming loads the decode kernels use for weights, and writes a checksum per workgroup to sink (device,
+ * at least 16384 bytes, 4-byte aligned; CQIL_ESIZE if sink_bytes is smaller).  Timed by the caller, it gives the
+ * read-only stream rate of this GPU: the practical ceiling of the bandwidth-bound kernels.  Asynchronous. */
+int cqil_stream_read_probe(const void *buf, size_t bytes, void *sink, size_t sink_bytes, void *stream);
+
 /* Whole model (Alg.1 around LLaMA's embedding, final RMSNorm and lm head). */
 typedef struct {
     cqil_dims dims;

@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
         L.cqil_group_forward.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_void_p, C.POINTER(cqil_kv),
                                          C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
+        L.cqil_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
         L.cqil_static_scratch_bytes.restype = C.c_size_t
         L.cqil_static_scratch_bytes.argtypes = []
         L.cqil_group_forward_static.argtypes = [C.POINTER(cqil_dims), C.c_int, C.c_int, C.c_void_p, C.POINTER(cqil_kv),
@@ -188,6 +189,14 @@ def cqil_group_forward(dims: cqil_dims, P: int, bypass_d: int, packed: torch.Ten
                                   workspace.numel() * workspace.element_size(), _stream())
     if rc:
         raise CqilError(rc, "cqil_group_forward")
+
+
+def cqil_stream_read_probe(buf: torch.Tensor, sink: torch.Tensor) -> None:
+    """Reads every byte of buf once (measurement aid); sink: device tensor of at least 16384 bytes."""
+    rc = lib().cqil_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink),
+                                      sink.numel() * sink.element_size(), _stream())
+    if rc:
+        raise CqilError(rc, "cqil_stream_read_probe")
 
 
 def cqil_static_scratch_bytes() -> int:

@@ -296,6 +296,15 @@ int cqil_group_forward(const cqil_dims* dims, int P, int bypass_d, const void* p
     return rc;
 }
 
+int cqil_stream_read_probe(const void* buf, size_t bytes, void* sink, size_t sink_bytes, void* stream) {
+    if (!buf || !sink || bytes < 16 || (bytes & 15)) return CQIL_EINVAL;
+    if (!aligned16(buf) || ((uintptr_t)sink & 3)) return CQIL_EINVAL;
+    if (sink_bytes < (size_t)kStreamProbeWorkgroups * sizeof(uint32_t)) return CQIL_ESIZE;
+    return launch_stream_read(buf, bytes, (uint32_t*)sink, kStreamProbeWorkgroups, (hipStream_t)stream) == hipSuccess
+               ? CQIL_OK
+               : CQIL_EHIP;
+}
+
 size_t cqil_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int cqil_group_forward_static(const cqil_dims* dims, int P, int bypass_d, const void* packed, cqil_kv* kv,

@@ -67,6 +67,9 @@ hipError_t launch_merge_lora(void* W, const void* A, const void* Bm, int dtype, 
 hipError_t launch_similarity(const void* X, int dtype, int L, int M, int n, float* sim, float* part, int chunks,
                              int tokens_per_chunk, hipStream_t st);
 
+constexpr int kStreamProbeWorkgroups = 4096;  // sink of cqil_stream_read_probe: this many uint32
+hipError_t launch_stream_read(const void* buf, size_t bytes, uint32_t* sink, int workgroups, hipStream_t st);
+
 struct StepArgs {
     cqil_dims d;
     int P, bypass_d, B, T, advance;

@@ -241,4 +241,36 @@ hipError_t launch_similarity(const void* X, int dtype, int L, int M, int n, floa
     return hipGetLastError();
 }
 
+// Measurement aid: reads n 16-byte chunks once with the streaming (non-temporal) loads of the decode kernels.  A
+// workgroup takes tiles of 256 x 8 consecutive chunks (every load instruction of a wave reads 1 KiB of consecutive
+// bytes, eight in flight per thread, the way the decode kernels walk their weight tiles), every index checked against
+// n.  The xor of what was read goes to sink[workgroup] so that the loads cannot be dropped.  Gives the rate at which
+// this GPU delivers a read-only stream, the ceiling the decode kernels are compared with besides the nameplate.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ buf, size_t n, uint32_t* __restrict__ sink) {
+    constexpr int U = 8;
+    __shared__ uint32_t ws[4];
+    const size_t tile = (size_t)256 * U;
+    uint32_t acc = 0;
+    for (size_t base = (size_t)blockIdx.x * tile; base < n; base += (size_t)gridDim.x * tile) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t i = base + (size_t)u * 256 + threadIdx.x;
+            v[u] = (i < n) ? load16_stream(buf + i) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc ^= __shfl_xor(acc, off, kWave);
+    if ((threadIdx.x & 63) == 0) ws[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = ws[0] ^ ws[1] ^ ws[2] ^ ws[3];
+}
+
+hipError_t launch_stream_read(const void* buf, size_t bytes, uint32_t* sink, int workgroups, hipStream_t st) {
+    hipLaunchKernelGGL(stream_read_kernel, dim3(workgroups), dim3(256), 0, st, (const uint4*)buf, bytes / 16, sink);
+    return hipGetLastError();
+}
+
 }  // namespace cqil

@@ -155,6 +155,15 @@ def test_static_scratch_entry_point_validates_before_any_gpu_call():
     assert 0 < cq.cqil_workspace_bytes(dims("33b", torch.bfloat16, 2048), 16, 1, 1) <= lib.cqil_static_scratch_bytes()
 
 
+def test_stream_read_probe_validates_before_launching():
+    lib = cq.lib()
+    assert lib.cqil_stream_read_probe(None, 1024, 0x1000, 16384, None) == cq.CQIL_EINVAL
+    assert lib.cqil_stream_read_probe(0x1000, 1000, 0x1000, 16384, None) == cq.CQIL_EINVAL      # not a multiple of 16
+    assert lib.cqil_stream_read_probe(0x1008, 1024, 0x1000, 16384, None) == cq.CQIL_EINVAL      # misaligned
+    assert lib.cqil_stream_read_probe(0x1000, 0, 0x1000, 16384, None) == cq.CQIL_EINVAL
+    assert lib.cqil_stream_read_probe(0x1000, 1024, 0x1000, 16380, None) == cq.CQIL_ESIZE
+
+
 def test_set_tuning_error_returns_and_reset():
     lib = cq.lib()
     assert lib.cqil_set_tuning(None, 1) == cq.CQIL_EINVAL

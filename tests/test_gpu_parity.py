@@ -106,6 +106,21 @@ def test_pack_group_is_a_bit_exact_index_map(shape, P, dtype):
         assert (raw[a:b] == 0xAB).all()
 
 
+def test_stream_read_probe_reads_every_chunk_exactly_once():
+    """The measurement aid's checksum equals the xor of all 32-bit words of the buffer (each 16-byte chunk read once,
+    none beyond the end), for sizes around the kernel's stride and unroll."""
+    gen = synth.generator(77)
+    for n_chunks in (1, 255, 2047, 2049, 4096 * 2048 - 1, 4096 * 2048 + 13):
+        words = torch.randint(-2 ** 31, 2 ** 31 - 1, (n_chunks * 4 + 8,), generator=gen, dtype=torch.int64).to(torch.int32)
+        buf = words.cuda()
+        sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+        cq.cqil_stream_read_probe(buf[: n_chunks * 4], sink)
+        torch.cuda.synchronize()
+        got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+        exp = np.bitwise_xor.reduce(words.numpy()[: n_chunks * 4].view(np.uint32))
+        assert got == exp, f"{n_chunks} chunks"
+
+
 # ------------------------------------------------------------------------------------------ Sec.3.1 tooling
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_input_similarity_of_captured_layer_inputs(dtype):
