@@ -211,6 +211,18 @@ int cqil_model_forward(cqil_model *m /* host */, const int32_t *tokens, int B, i
                        int advance_kv_len, void *hidden_out, float *logits_out, int32_t *next_token_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* Input substitution (Sec.3.2, the sensitivity study that decides which layers may share an input): the model runs
+ * as cqil_model_forward does, except that group `group` (0-based index into group_sizes; a layer when every group has
+ * one layer, as in the paper's experiment) reads the input of group `group - k` instead of its own:
+ *   x_after = x_before + F_group(x_input_of(group - k)),   F = the group's attention and feed-forward branches,
+ * every other term unchanged, later groups see the changed state.  Its KV cache is filled from the substituted input.
+ * k == 0 is cqil_model_forward; 0 <= k <= group < n_groups, else CQIL_EINVAL.  workspace:
+ * cqil_model_substituted_workspace_bytes() bytes (one more hidden state than the plain model loop). */
+size_t cqil_model_substituted_workspace_bytes(const cqil_model *m /* host */, int B, int T);
+int cqil_model_forward_substituted(cqil_model *m /* host */, const int32_t *tokens, int B, int T, int bypass_d,
+                                   int advance_kv_len, int group, int k, void *hidden_out, float *logits_out,
+                                   int32_t *next_token_out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Launch-shape knobs (process-wide, host-only, not thread-safe; set them
  * before sizing workspaces).  Keys: "ksplit_qkv", "ksplit_o", "ksplit_gu", "ksplit_d" (waves that share one unit
  * of work and split its k range in the QKV / O / gate-up / down kernel: 1, 2, 4 or 8; 0 = chosen by shape),

@@ -19,7 +19,12 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "cqil_oracle.c")
-_LIB = os.path.join(_HERE, "libcqil_oracle.so")
+# CQIL_ORACLE_SANITIZE=1 builds and loads an AddressSanitizer + UndefinedBehaviorSanitizer build of the oracle (host code
+# only).  The sanitizer runtime has to be in the process before python starts:
+#   LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 CQIL_ORACLE_SANITIZE=1 \
+#       python -m pytest tests -m "not gpu"
+SANITIZE = os.environ.get("CQIL_ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "libcqil_oracle_san.so" if SANITIZE else "libcqil_oracle.so")
 
 F32, BF16 = 0, 1
 
@@ -27,8 +32,10 @@ F32, BF16 = 0, 1
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (OpenMP for independent rows/heads only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-g",
+               "-O1"] if SANITIZE else ["-O2"]
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, "-lm"]
+            ["gcc", *san, "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, "-lm"]
         )
     return _LIB
 
@@ -255,8 +262,9 @@ def partition(L: int, p: int, s: int, e: int) -> list:
 
 def model_forward(dims: Dims, layers: Sequence[dict], group_sizes: Sequence[int], d: int,
                   embedding: np.ndarray, g_final: np.ndarray, lm_head: np.ndarray,
-                  kcache, vcache, kv_len, tokens, want_logits: bool = True):
-    """Alg.1 around the LLaMA embedding / final norm / lm head.
+                  kcache, vcache, kv_len, tokens, want_logits: bool = True, sub_group: int = -1, sub_k: int = 0):
+    """Alg.1 around the LLaMA embedding / final norm / lm head.  With sub_group >= 0: Sec.3.2's input substitution
+    (group sub_group reads the input of group sub_group - sub_k).
     Returns dict(hidden [B,T,dm], logits [B,V] of the last position, next [B])."""
     tokens = np.ascontiguousarray(tokens, dtype=np.int32)
     B, T = tokens.shape
@@ -271,9 +279,15 @@ def model_forward(dims: Dims, layers: Sequence[dict], group_sizes: Sequence[int]
     hidden = np.empty((B, T, dims.d_model))
     logits = np.empty((B, V)) if want_logits else None
     nxt = np.empty(B, dtype=np.int32)
-    rc = lib().orc_model_forward(C.byref(dims.c()), L, arr, len(group_sizes), gs, d, _p(embedding),
-                                 _p(g_final), _p(lm_head), V, _p(kcache), _p(vcache), kcache.shape[1],
-                                 _p(kv), _p(tokens), B, T, _p(hidden), _p(logits), _p(nxt))
+    if sub_group >= 0:
+        rc = lib().orc_model_forward_substituted(C.byref(dims.c()), L, arr, len(group_sizes), gs, d, int(sub_group),
+                                                 int(sub_k), _p(embedding), _p(g_final), _p(lm_head), V, _p(kcache),
+                                                 _p(vcache), kcache.shape[1], _p(kv), _p(tokens), B, T, _p(hidden),
+                                                 _p(logits), _p(nxt))
+    else:
+        rc = lib().orc_model_forward(C.byref(dims.c()), L, arr, len(group_sizes), gs, d, _p(embedding),
+                                     _p(g_final), _p(lm_head), V, _p(kcache), _p(vcache), kcache.shape[1],
+                                     _p(kv), _p(tokens), B, T, _p(hidden), _p(logits), _p(nxt))
     if rc:
         raise RuntimeError(f"orc_model_forward rc={rc}")
     return {"hidden": hidden, "logits": logits, "next": nxt}

@@ -20,6 +20,7 @@
  *   orc_group_forward Eq.3 (d = 0) and Eq.4 (bypass distance d), Alg.1's middle loop
  *   orc_partition     Sec.4.2 "Layer Partition and Parallelism": (p, s, e) -> group sizes
  *   orc_model_forward Alg.1 as a whole, with the LLaMA embedding / final norm / lm head around it
+ *   orc_model_forward_substituted   the input-substitution experiment of Sec.3.2 on that model
  *
  * Readings taken where the paper is silent or inconsistent (the same list is in the design
  * document): the bypass window is Eq.4's index set {l' : 1 <= l-l' <= d} (Alg.1's slice
@@ -384,15 +385,49 @@ int orc_partition(int L, int p, int s, int e, int *group_sizes) {
  *   next_out     optional [B]
  * kv_len is not advanced here.
  */
+static int model_forward_subst(const orc_dims *D, int L, const orc_layer *layers, int n_groups,
+                               const int *group_sizes, int d, int sub_group, int sub_k, const void *embedding,
+                               const void *g_final, const void *lm_head, int vocab, double *kcache, double *vcache,
+                               int b_max, const int32_t *kv_len, const int32_t *tokens, int B, int T,
+                               double *hidden_out, double *logits_out, int32_t *next_out);
+
 int orc_model_forward(const orc_dims *D, int L, const orc_layer *layers, int n_groups,
                       const int *group_sizes, int d, const void *embedding, const void *g_final,
                       const void *lm_head, int vocab, double *kcache, double *vcache, int b_max,
                       const int32_t *kv_len, const int32_t *tokens, int B, int T, double *hidden_out,
                       double *logits_out, int32_t *next_out) {
+    return model_forward_subst(D, L, layers, n_groups, group_sizes, d, -1, 0, embedding, g_final, lm_head, vocab, kcache,
+                               vcache, b_max, kv_len, tokens, B, T, hidden_out, logits_out, next_out);
+}
+
+/*
+ * Input substitution (Sec.3.2): with the model written as x_{L+1} = x_1 + F_1(x_1) + ... + F_L(x_L), the input of
+ * one F is replaced by the input of an earlier one and every other term is kept: here F is the update of group
+ * sub_group (a layer when every group has one layer) and it reads the input of group sub_group - sub_k,
+ *   x_after = x_before + ( group_forward(x_input_of(sub_group - sub_k)) - x_input_of(sub_group - sub_k) ),
+ * later groups see the changed state; the group's caches are filled from the substituted input.
+ * sub_k = 0 is the plain model.  Requires 0 <= sub_k <= sub_group < n_groups.
+ */
+int orc_model_forward_substituted(const orc_dims *D, int L, const orc_layer *layers, int n_groups,
+                                  const int *group_sizes, int d, int sub_group, int sub_k, const void *embedding,
+                                  const void *g_final, const void *lm_head, int vocab, double *kcache, double *vcache,
+                                  int b_max, const int32_t *kv_len, const int32_t *tokens, int B, int T,
+                                  double *hidden_out, double *logits_out, int32_t *next_out) {
+    if (sub_group < 0 || sub_group >= n_groups || sub_k < 0 || sub_k > sub_group) return -1;
+    return model_forward_subst(D, L, layers, n_groups, group_sizes, d, sub_group, sub_k, embedding, g_final, lm_head,
+                               vocab, kcache, vcache, b_max, kv_len, tokens, B, T, hidden_out, logits_out, next_out);
+}
+
+static int model_forward_subst(const orc_dims *D, int L, const orc_layer *layers, int n_groups,
+                               const int *group_sizes, int d, int sub_group, int sub_k, const void *embedding,
+                               const void *g_final, const void *lm_head, int vocab, double *kcache, double *vcache,
+                               int b_max, const int32_t *kv_len, const int32_t *tokens, int B, int T,
+                               double *hidden_out, double *logits_out, int32_t *next_out) {
     const int dm = D->d_model;
     size_t n = (size_t)B * (size_t)T * (size_t)dm;
     double *x = malloc(sizeof(double) * n), *y = malloc(sizeof(double) * n);
-    if (!x || !y) return -2;
+    double *xs = malloc(sizeof(double) * n); /* input of group sub_group - sub_k */
+    if (!x || !y || !xs) return -2;
     for (int m = 0; m < B * T; ++m) {
         int32_t tok = tokens[m];
         if (tok < 0 || tok >= vocab) return -4;
@@ -403,9 +438,14 @@ int orc_model_forward(const orc_dims *D, int L, const orc_layer *layers, int n_g
     for (int g = 0; g < n_groups; ++g) {
         int P = group_sizes[g];
         if (P < 1 || l0 + P > L) return -1;
+        const int subst = sub_group >= 0 && sub_k > 0;
+        if (subst && g == sub_group - sub_k) memcpy(xs, x, sizeof(double) * n);
+        const double *in = (subst && g == sub_group) ? xs : x;
         int rc = orc_group_forward(D, P, d, layers + l0, kcache + per_layer * (size_t)l0,
-                                   vcache + per_layer * (size_t)l0, b_max, kv_len, x, y, B, T, NULL, NULL);
+                                   vcache + per_layer * (size_t)l0, b_max, kv_len, in, y, B, T, NULL, NULL);
         if (rc) return rc;
+        if (subst && g == sub_group)   /* the group's update F(xs) = y - xs, added to the current state */
+            for (size_t e = 0; e < n; ++e) y[e] = x[e] + (y[e] - xs[e]);
         double *tmp = x; x = y; y = tmp;
         l0 += P;
     }
@@ -429,6 +469,6 @@ int orc_model_forward(const orc_dims *D, int L, const orc_layer *layers, int n_g
         }
         free(nrm); free(lg);
     }
-    free(x); free(y);
+    free(x); free(y); free(xs);
     return 0;
 }

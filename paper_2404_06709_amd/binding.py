@@ -99,6 +99,11 @@ def lib() -> C.CDLL:
         L.cqil_model_workspace_bytes.argtypes = [C.POINTER(cqil_model), C.c_int, C.c_int]
         L.cqil_model_forward.argtypes = [C.POINTER(cqil_model), C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.cqil_model_substituted_workspace_bytes.restype = C.c_size_t
+        L.cqil_model_substituted_workspace_bytes.argtypes = [C.POINTER(cqil_model), C.c_int, C.c_int]
+        L.cqil_model_forward_substituted.argtypes = [C.POINTER(cqil_model), C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                     C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                     C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
 
@@ -300,3 +305,20 @@ def cqil_model_forward(model: Model, tokens: torch.Tensor, B: int, T: int, bypas
                                   workspace.numel() * workspace.element_size(), _stream())
     if rc:
         raise CqilError(rc, "cqil_model_forward")
+
+
+def cqil_model_substituted_workspace_bytes(model: Model, B: int, T: int) -> int:
+    return int(lib().cqil_model_substituted_workspace_bytes(C.byref(model.c), B, T))
+
+
+def cqil_model_forward_substituted(model: Model, tokens: torch.Tensor, B: int, T: int, bypass_d: int,
+                                   advance_kv_len: bool, group: int, k: int, hidden_out: Optional[torch.Tensor],
+                                   logits_out: Optional[torch.Tensor], next_token_out: Optional[torch.Tensor],
+                                   workspace: torch.Tensor) -> None:
+    """Sec.3.2: group `group` reads the input of group `group - k`; everything else as cqil_model_forward."""
+    assert tokens.dtype == torch.int32
+    rc = lib().cqil_model_forward_substituted(C.byref(model.c), _ptr(tokens), B, T, bypass_d, 1 if advance_kv_len else 0,
+                                              group, k, _ptr(hidden_out), _ptr(logits_out), _ptr(next_token_out),
+                                              _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc:
+        raise CqilError(rc, "cqil_model_forward_substituted")

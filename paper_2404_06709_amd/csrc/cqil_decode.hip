@@ -382,7 +382,7 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
                            s.wl.down_slice, ks_d);
     }
     CQIL_MARK(5);
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 255) / 256, 1), dim3(256), 0, st, (const T*)s.x_in,
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 255) / 256, 1), dim3(256), 0, st, (const T*)s.x_res,
                        a, dpart, (T*)s.x_out, s.kv_len, s.advance, P, s.wl.n_slices, 1, dm, 1, 1);
     CQIL_MARK(6);
 #undef CQIL_MARK

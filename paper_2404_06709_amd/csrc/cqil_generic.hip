@@ -202,10 +202,12 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
 }
 
 // Bypass window, FFN norms and the residual carrier for one token row per workgroup:
-//   h_i = x + sum_{j=max(0,i-d)}^{i} a_j ; nrm_i = RMSNorm(h_i) g_i ; resid = x + sum_j a_j
+//   h_i = x + sum_{j=max(0,i-d)}^{i} a_j ; nrm_i = RMSNorm(h_i) g_i ; resid = xres + sum_j a_j
+// (xres is x itself except under input substitution, where the branches computed from x are added to another state)
 // 16-byte accesses: a thread owns chunks of kVec consecutive elements (d_model % kVec == 0).
 template <typename T>
-__global__ __launch_bounds__(1024) void bypass_norm_kernel(const T* __restrict__ x, const float* __restrict__ a,
+__global__ __launch_bounds__(1024) void bypass_norm_kernel(const T* __restrict__ x, const T* __restrict__ xres,
+                                                          const float* __restrict__ a,
                                                           const T* __restrict__ g_ffn, T* __restrict__ nrm,
                                                           float* __restrict__ resid, int P, int bypass_d, int M,
                                                           int d_model, float eps, int32_t* __restrict__ kv_len,
@@ -214,10 +216,11 @@ __global__ __launch_bounds__(1024) void bypass_norm_kernel(const T* __restrict__
     __shared__ float scratch[16];
     const int m = blockIdx.x, tid = threadIdx.x;
     const T* xr = x + (size_t)m * d_model;
+    const T* xrr = xres + (size_t)m * d_model;
     const int n_chunks = d_model / V;
     // h_i for the chunk at k: x plus the window of attention outputs
-    auto window = [&](int k, int jlo, int jhi, float (&hv)[V]) {
-        elem<T>::unpack(load16(xr + k), hv);
+    auto window = [&](const T* base, int k, int jlo, int jhi, float (&hv)[V]) {
+        elem<T>::unpack(load16(base + k), hv);
         for (int j = jlo; j <= jhi; ++j) {
             const float* ap = a + ((size_t)j * M + m) * d_model + k;
 #pragma unroll
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(1024) void bypass_norm_kernel(const T* __restrict__
         float ss = 0.f;
         for (int c = tid; c < n_chunks; c += blockDim.x) {
             float hv[V];
-            window(c * V, jlo, i, hv);
+            window(xr, c * V, jlo, i, hv);
 #pragma unroll
             for (int e = 0; e < V; ++e) ss += hv[e] * hv[e];
         }
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(1024) void bypass_norm_kernel(const T* __restrict__
         T* out = nrm + ((size_t)i * M + m) * d_model;
         for (int c = tid; c < n_chunks; c += blockDim.x) {
             float hv[V], gv[V];
-            window(c * V, jlo, i, hv);
+            window(xr, c * V, jlo, i, hv);
             elem<T>::unpack(load16(gi + c * V), gv);
 #pragma unroll
             for (int e = 0; e < V; ++e) hv[e] = hv[e] * r * gv[e];
@@ -254,7 +257,7 @@ __global__ __launch_bounds__(1024) void bypass_norm_kernel(const T* __restrict__
         for (int b = tid; b < advance_B; b += blockDim.x) kv_len[b] += advance_T;
     for (int c = tid; c < n_chunks; c += blockDim.x) {
         float hv[V];
-        window(c * V, 0, P - 1, hv);
+        window(xrr, c * V, 0, P - 1, hv);
 #pragma unroll
         for (int e = 0; e < V; e += 4)
             *reinterpret_cast<float4*>(resid + (size_t)m * d_model + c * V + e) = make_float4(hv[e], hv[e + 1], hv[e + 2], hv[e + 3]);
@@ -266,7 +269,8 @@ __global__ __launch_bounds__(1024) void bypass_norm_kernel(const T* __restrict__
 // (the general kernel re-reads the window in every pass).  blockDim.x >= d_model / V, a multiple of 64.
 constexpr int kBypassRegLayers = 8;
 template <typename T>
-__global__ __launch_bounds__(1024) void bypass_norm_reg_kernel(const T* __restrict__ x, const float* __restrict__ a,
+__global__ __launch_bounds__(1024) void bypass_norm_reg_kernel(const T* __restrict__ x, const T* __restrict__ xres,
+                                                              const float* __restrict__ a,
                                                               const T* __restrict__ g_ffn, T* __restrict__ nrm,
                                                               float* __restrict__ resid, int P, int bypass_d, int M,
                                                               int d_model, float eps, int32_t* __restrict__ kv_len,
@@ -322,6 +326,7 @@ __global__ __launch_bounds__(1024) void bypass_norm_reg_kernel(const T* __restri
     if (advance_B > 0 && m == 0)
         for (int b = tid; b < advance_B; b += blockDim.x) kv_len[b] += advance_T;
     if (act) {
+        if (xres != x) elem<T>::unpack(load16(xres + (size_t)m * d_model + k), xv);  // wave-uniform
 #pragma unroll
         for (int j = 0; j < kBypassRegLayers; ++j)
 #pragma unroll
@@ -441,6 +446,17 @@ __global__ void advance_kernel(int32_t* kv_len, int B, int T) {
     if (b < B) kv_len[b] += T;
 }
 
+__global__ void copy16_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+hipError_t launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t st) {
+    const size_t n = bytes / 16;
+    const unsigned grid = (unsigned)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256);
+    hipLaunchKernelGGL(copy16_kernel, dim3(grid ? grid : 1), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_advance(int32_t* kv_len, int B, int T, hipStream_t st) {
     hipLaunchKernelGGL(advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, kv_len, B, T);
     return hipGetLastError();
@@ -537,9 +553,9 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
                                         part, s.wl.gemm_part_floats)) != hipSuccess) return ge;
     if (P <= kBypassRegLayers && dm / elem<T>::kVec <= 1024)
         hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_reg_kernel<T>), dim3(M), dim3((dm / elem<T>::kVec + 63) / 64 * 64), 0,
-                           st, x, a, g_ffn, nrm, resid, P, bd, M, dm, d.rms_eps, s.kv_len, s.advance ? s.B : 0, s.T);
+                           st, x, (const T*)s.x_res, a, g_ffn, nrm, resid, P, bd, M, dm, d.rms_eps, s.kv_len, s.advance ? s.B : 0, s.T);
     else
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(row_threads), 0, st, x, a, g_ffn, nrm,
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(bypass_norm_kernel<T>), dim3(M), dim3(row_threads), 0, st, x, (const T*)s.x_res, a, g_ffn, nrm,
                            resid, P, bd, M, dm, d.rms_eps, s.kv_len, s.advance ? s.B : 0, s.T);
     if constexpr (std::is_same<T, bf16_t>::value) {
         // gate/up product with SwiGLU in the epilogue: u is written directly, gate and up never reach memory

@@ -218,7 +218,7 @@ int cqil_pack_group(const cqil_dims* dims, int P, const cqil_layer* layers, void
 static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const void* packed, void* kc, void* vc,
                               int32_t* kv_len, int b_max, int max_kv_len, const void* x_in, void* x_out, int B, int T,
                               int advance, void* workspace, size_t workspace_bytes, hipStream_t st,
-                              hipEvent_t* ev = nullptr, bool check_only = false) {
+                              hipEvent_t* ev = nullptr, bool check_only = false, const void* x_res = nullptr) {
     StepArgs a;
     a.ev = ev;
     int rc = packed_layout(dims, P, &a.pl);
@@ -226,7 +226,7 @@ static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const 
     if (bypass_d < CQIL_ATTN_FFN_PARALLEL || B < 1 || T < 1) return CQIL_EINVAL;
     if (!packed || !kc || !vc || !kv_len || !x_in || !x_out || !workspace) return CQIL_EINVAL;
     if (!aligned16(packed) || !aligned16(kc) || !aligned16(vc) || !aligned16(x_in) || !aligned16(x_out) ||
-        !aligned16(workspace))
+        !aligned16(workspace) || !aligned16(x_res))
         return CQIL_EINVAL;
     if (b_max < 1 || max_kv_len < 0) return CQIL_EINVAL;
     if (B > b_max) return CQIL_ERANGE;
@@ -238,7 +238,7 @@ static int group_forward_impl(const cqil_dims* dims, int P, int bypass_d, const 
     a.d = *dims; a.P = P; a.bypass_d = bypass_d; a.B = B; a.T = T; a.advance = advance ? 1 : 0;
     a.packed = (const char*)packed;
     a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.b_max = b_max; a.max_kv_len = max_kv_len;
-    a.x_in = x_in; a.x_out = x_out; a.ws = (char*)workspace;
+    a.x_in = x_in; a.x_res = x_res ? x_res : x_in; a.x_out = x_out; a.ws = (char*)workspace;
     hipError_t e = (B * T == 1) ? launch_decode_step(a, st) : launch_generic_step(a, st);
     return e == hipSuccess ? CQIL_OK : CQIL_EHIP;
 }
@@ -375,9 +375,10 @@ size_t cqil_model_workspace_bytes(const cqil_model* m, int B, int T) {
     return model_ws(m, B, T, &a, &b, &c, &d, &t) ? 0 : t;
 }
 
-int cqil_model_forward(cqil_model* m, const int32_t* tokens, int B, int T, int bypass_d, int advance_kv_len,
-                       void* hidden_out, float* logits_out, int32_t* next_token_out, void* workspace,
-                       size_t workspace_bytes, void* stream) {
+// Model loop shared by cqil_model_forward (sub_group < 0) and cqil_model_forward_substituted.
+static int model_forward_impl(cqil_model* m, const int32_t* tokens, int B, int T, int bypass_d, int advance_kv_len,
+                              int sub_group, int sub_k, void* hidden_out, float* logits_out, int32_t* next_token_out,
+                              void* workspace, size_t workspace_bytes, void* stream) {
     size_t x_off, lg_off, sc_off, g_off, total;
     int rc = model_ws(m, B, T, &x_off, &lg_off, &sc_off, &g_off, &total);
     if (rc) return rc;
@@ -388,12 +389,16 @@ int cqil_model_forward(cqil_model* m, const int32_t* tokens, int B, int T, int b
     if (!aligned16(workspace) || !aligned16(m->embedding) || !aligned16(m->lm_head) || !aligned16(m->g_final))
         return CQIL_EINVAL;
     if (hidden_out && !aligned16(hidden_out)) return CQIL_EINVAL;
-    if (workspace_bytes < total) return CQIL_ESIZE;
+    const bool subst = sub_group >= 0 && sub_k > 0;
+    if (sub_group >= 0 && (sub_group >= m->n_groups || sub_k < 0 || sub_k > sub_group)) return CQIL_EINVAL;
+    const size_t x_bytes = align_up((size_t)B * T * m->dims.d_model * esize(m->dims.dtype));
+    if (workspace_bytes < total + (subst ? x_bytes : 0)) return CQIL_ESIZE;
     if (B > m->b_max) return CQIL_ERANGE;
     if ((long long)m->max_kv_len + T > m->dims.max_seq) return CQIL_ERANGE;
     hipStream_t st = (hipStream_t)stream;
     char* ws = (char*)workspace;
     void* x = hidden_out ? hidden_out : (void*)(ws + x_off);
+    void* x_sub = ws + total;   // the captured input of group sub_group - sub_k
     const size_t gbytes = total - g_off;
     // every group is checked (pointers, alignment, ranges, workspace) before the first launch
     for (int g = 0; g < m->n_groups; ++g) {
@@ -404,8 +409,14 @@ int cqil_model_forward(cqil_model* m, const int32_t* tokens, int B, int T, int b
 
     if (launch_embedding(m->dims, m->embedding, tokens, B * T, m->vocab, x, st) != hipSuccess) return CQIL_EHIP;
     for (int g = 0; g < m->n_groups; ++g) {
+        if (subst && g == sub_group - sub_k &&
+            launch_copy16(x, x_sub, (size_t)B * T * m->dims.d_model * esize(m->dims.dtype), st) != hipSuccess)
+            return CQIL_EHIP;
+        const bool here = subst && g == sub_group;
+        // substituted group: its branches are computed from the captured state and added to the current one
         rc = group_forward_impl(&m->dims, m->group_sizes[g], bypass_d, m->packed[g], m->k_cache[g], m->v_cache[g],
-                                m->kv_len, m->b_max, m->max_kv_len, x, x, B, T, 0, ws + g_off, gbytes, st);
+                                m->kv_len, m->b_max, m->max_kv_len, here ? x_sub : x, x, B, T, 0, ws + g_off, gbytes, st,
+                                nullptr, false, here ? x : nullptr);
         if (rc) return rc;
     }
     if (logits_out || next_token_out) {
@@ -422,6 +433,26 @@ int cqil_model_forward(cqil_model* m, const int32_t* tokens, int B, int T, int b
         m->max_kv_len += T;
     }
     return CQIL_OK;
+}
+
+int cqil_model_forward(cqil_model* m, const int32_t* tokens, int B, int T, int bypass_d, int advance_kv_len,
+                       void* hidden_out, float* logits_out, int32_t* next_token_out, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+    return model_forward_impl(m, tokens, B, T, bypass_d, advance_kv_len, -1, 0, hidden_out, logits_out, next_token_out,
+                              workspace, workspace_bytes, stream);
+}
+
+size_t cqil_model_substituted_workspace_bytes(const cqil_model* m, int B, int T) {
+    const size_t base = cqil_model_workspace_bytes(m, B, T);
+    return base ? base + align_up((size_t)B * T * m->dims.d_model * esize(m->dims.dtype)) : 0;
+}
+
+int cqil_model_forward_substituted(cqil_model* m, const int32_t* tokens, int B, int T, int bypass_d, int advance_kv_len,
+                                   int group, int k, void* hidden_out, float* logits_out, int32_t* next_token_out,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    if (group < 0) return CQIL_EINVAL;
+    return model_forward_impl(m, tokens, B, T, bypass_d, advance_kv_len, group, k, hidden_out, logits_out,
+                              next_token_out, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -79,6 +79,7 @@ struct StepArgs {
     int32_t* kv_len;
     int b_max, max_kv_len;
     const void* x_in;
+    const void* x_res;  // state the branches are added to (x_in itself, or another state under input substitution)
     void* x_out;
     char* ws;
     WsLayout wl;
@@ -102,5 +103,6 @@ hipError_t launch_embedding(const cqil_dims& d, const void* emb, const int32_t* 
                             hipStream_t st);
 hipError_t launch_head(const HeadArgs& a, hipStream_t st);
 hipError_t launch_advance(int32_t* kv_len, int B, int T, hipStream_t st);
+hipError_t launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t st);  // bytes % 16 == 0
 
 }  // namespace cqil

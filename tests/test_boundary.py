@@ -240,6 +240,28 @@ def test_model_forward_validates_before_launching():
     assert lib.cqil_model_workspace_bytes(C.byref(m), 1, 4) == 0
 
 
+def test_substituted_model_forward_validates_before_launching():
+    d = dims()
+    n = 3
+    gs = (C.c_int * n)(1, 2, 1)
+    ptrs = (C.c_void_p * n)(0x1000, 0x1000, 0x1000)
+    m = cq.cqil_model(d, 100, n, gs, ptrs, ptrs, ptrs, 0x1000, 1, 0, 0x1000, 0x1000, 0x1000)
+    lib = cq.lib()
+    need = lib.cqil_model_substituted_workspace_bytes(C.byref(m), 1, 4)
+    assert need == lib.cqil_model_workspace_bytes(C.byref(m), 1, 4) + 4 * 256 * 4
+
+    def call(group, k, nbytes=need, tokens=0x1000):
+        return lib.cqil_model_forward_substituted(C.byref(m), tokens, 1, 4, 1, 0, group, k, None, None, None, 0x1000,
+                                                  nbytes, None)
+
+    assert call(-1, 0) == cq.CQIL_EINVAL
+    assert call(3, 1) == cq.CQIL_EINVAL          # no such group
+    assert call(1, 2) == cq.CQIL_EINVAL          # reaches before the first group
+    assert call(2, -1) == cq.CQIL_EINVAL
+    assert call(2, 1, tokens=None) == cq.CQIL_EINVAL
+    assert call(2, 1, nbytes=need - 1) == cq.CQIL_ESIZE
+
+
 def test_bench_refuses_more_than_one_gpu():
     """This build runs on one GPU: bench.py --gpus N with N > 1 exits with a message, before touching any device."""
     import subprocess

@@ -572,6 +572,55 @@ def test_model_forward_general_partitions(L, p, s, e):
         tokens = torch.from_numpy(ref["next"].reshape(1, 1).astype(np.int32))
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_model_forward_with_input_substitution(dtype):
+    """Sec.3.2 through cqil_model_forward_substituted: a 5-layer model of single layers (the paper's experiment) with
+    layer 4 reading the input of layers 3 / 2 / 1, and a grouped partition with a group reading an earlier group's
+    input; an 11-token prompt (token-parallel kernels) and two single-token steps (decode kernels), hidden state,
+    logits and the substituted layer's KV cache against the oracle; k = 0 equals cqil_model_forward bit for bit."""
+    vocab, max_seq = 509, 32
+    for sizes, grp, ks in (([1, 1, 1, 1, 1], 3, (1, 2, 3)), ([1, 2, 2], 2, (1, 2))):
+        L = sum(sizes)
+        for k in ks:
+            model, groups, kv_len, nl, emb, gfin, head = _tiny_model(dtype, sizes, vocab, max_seq, seed=5200 + L)
+            od = odims(TINY, max_seq, dtype)
+            okc, ovc = orc.new_cache(L, 1, od), orc.new_cache(L, 1, od)
+            tokens = torch.randint(0, vocab, (1, 11), generator=synth.generator(4)).to(torch.int32)
+            olen = 0
+            for step in range(3):
+                T = tokens.shape[1]
+                gws = Guarded(cq.cqil_model_substituted_workspace_bytes(model, 1, T))
+                logits = torch.empty(1, vocab, dtype=torch.float32, device="cuda")
+                hid = torch.empty(1, T, TINY.d_model, dtype=dtype, device="cuda")
+                cq.cqil_model_forward_substituted(model, tokens.cuda(), 1, T, 1, True, grp, k, hid, logits, None, gws.body)
+                torch.cuda.synchronize()
+                gws.check(f"substituted model {sizes} k={k}")
+                ref = orc.model_forward(od, nl, sizes, 1, emb, gfin, head, okc, ovc, [olen], tokens.numpy(),
+                                        sub_group=grp, sub_k=k)
+                plain = orc.model_forward(od, nl, sizes, 1, emb, gfin, head, okc.copy(), ovc.copy(), [olen], tokens.numpy())
+                e_h = rel_err(synth.widen(hid.cpu()), ref["hidden"])
+                e_l = rel_err(logits.cpu().numpy(), ref["logits"])
+                l0 = sum(sizes[:grp])
+                e_k = rel_err(synth.widen(groups[grp].k[:, 0, :, olen:olen + T].cpu()), okc[l0:l0 + sizes[grp], 0, :, olen:olen + T])
+                sep = rel_err(plain["hidden"], ref["hidden"])
+                say(f"  substitution {sizes} group {grp} k={k} {dtype} step {step}: hidden {e_h:.2e} logits {e_l:.2e} "
+                    f"cache {e_k:.2e} (plain model differs by {sep:.2e})")
+                assert max(e_h, e_l, e_k) <= TOL[dtype]
+                assert sep > 4 * TOL[dtype], "the substitution is not visible in this test"
+                olen += T
+                tokens = torch.from_numpy(ref["next"].reshape(1, 1).astype(np.int32))
+    # k = 0 is the plain model loop, bit for bit
+    model, groups, kv_len, *_ = _tiny_model(dtype, [1, 2, 1], vocab, max_seq, seed=5300)
+    tokens = torch.randint(0, vocab, (1, 5), generator=synth.generator(6)).to(torch.int32).cuda()
+    ws = torch.empty(cq.cqil_model_substituted_workspace_bytes(model, 1, 5), dtype=torch.uint8, device="cuda")
+    a = torch.empty(1, 5, TINY.d_model, dtype=dtype, device="cuda")
+    b = torch.empty_like(a)
+    cq.cqil_model_forward(model, tokens, 1, 5, 1, False, a, None, None, ws)
+    cq.cqil_model_forward_substituted(model, tokens, 1, 5, 1, False, 2, 0, b, None, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
 @pytest.mark.parametrize("vocab", [1003, 1024])
 def test_greedy_token_is_the_lowest_index_among_equal_maxima(vocab):
     """Ties in the logits (duplicated and all-zero rows of the lm head): the greedy token is the first maximum."""

@@ -576,6 +576,65 @@ def test_model_forward_is_the_chain_of_groups_with_embedding_and_head():
     assert np.abs(seq["hidden"] - res["hidden"]).max() > 1e-6    # CQIL is a different function
 
 
+def test_input_substitution_pins():
+    """Sec.3.2: x_{L+1} = x_1 + sum_l F_l(x_l) with the input of one F replaced by an earlier layer's input.
+    (i) k = 0 is the plain model bit for bit; (ii) the substituted model written out with the library modules for a
+    3-layer model; (iii) when the k layers in between add nothing (zero output projections) the substituted input
+    equals the true one and nothing changes; (iv) a real substitution changes the result and the layer's cache."""
+    D = tiny_dims()
+    Lnum, V = 4, 61
+    tl, nl = tiny_layers(Lnum, seed=1301)
+    gen = synth.generator(78)
+    emb = synth.to_numpy(synth.normal((V, D.d_model), 1.0, torch.float32, gen))
+    head = synth.to_numpy(synth.normal((V, D.d_model), 0.05, torch.float32, gen))
+    gfin = synth.to_numpy(1.0 + synth.normal((D.d_model,), 0.1, torch.float32, gen))
+    tokens = np.array([[7, 3, 60, 0, 12, 7]], dtype=np.int32)
+    sizes = [1] * Lnum
+
+    def run(layers, sub_group=-1, sub_k=0, gs=sizes):
+        kc, vc = orc.new_cache(Lnum, 1, D), orc.new_cache(Lnum, 1, D)
+        return orc.model_forward(D, layers, gs, 0, emb, gfin, head, kc, vc, [0], tokens, sub_group=sub_group, sub_k=sub_k), kc
+
+    plain, kc_plain = run(nl)
+    same, kc_same = run(nl, 2, 0)
+    np.testing.assert_array_equal(plain["hidden"], same["hidden"]); np.testing.assert_array_equal(kc_plain, kc_same)
+    np.testing.assert_array_equal(plain["logits"], same["logits"])
+    # (ii) layer 3 (index 2) reads the input of layer 2 (k = 1) / of layer 1 (k = 2), library modules
+    x1 = torch.from_numpy(emb[tokens[0]].astype(np.float64))
+    empty = torch.zeros(D.n_heads, 0, D.head_dim, dtype=torch.float64)
+
+    def F(i, x):
+        a = torch_attn(tl[i], x, empty, empty)[0]
+        return a + torch_ffn(tl[i], x + a)
+
+    x2 = x1 + F(0, x1)
+    x3 = x2 + F(1, x2)
+    for k, src in ((1, x2), (2, x1)):
+        x4 = x3 + F(2, src)
+        x5 = x4 + F(3, x4)
+        got, kc = run(nl, 2, k)
+        np.testing.assert_allclose(got["hidden"][0], x5.numpy(), rtol=1e-10, atol=1e-11)
+        assert np.abs(got["hidden"] - plain["hidden"]).max() > 1e-4            # (iv)
+        assert np.abs(kc[2] - kc_plain[2]).max() > 1e-4 and np.array_equal(kc[:2], kc_plain[:2])
+    # (iii) layers 2 and 3 silent: the input of layer 4 equals the inputs of layers 3 and 2
+    quiet = [dict(L) for L in nl]
+    for i in (1, 2):
+        quiet[i]["wo"] = np.zeros_like(quiet[i]["wo"]); quiet[i]["wdown"] = np.zeros_like(quiet[i]["wdown"])
+    base, _ = run(quiet)
+    for k in (1, 2):
+        sub, _ = run(quiet, 3, k)
+        np.testing.assert_allclose(sub["hidden"], base["hidden"], rtol=0, atol=1e-12)
+    # grouped partitions: a group reads the input of an earlier group
+    gsz = [1, 2, 1]
+    g_plain, _ = run(nl, gs=gsz)
+    g_sub, _ = run(nl, 2, 1, gs=gsz)
+    assert np.abs(g_sub["hidden"] - g_plain["hidden"]).max() > 1e-4
+    with pytest.raises(RuntimeError):
+        run(nl, 1, 2)                      # k reaches before the first layer
+    with pytest.raises(RuntimeError):
+        run(nl, 4, 1)                      # no such group
+
+
 def test_argmax_tie_break_is_lowest_index():
     D = tiny_dims()
     _, nl = tiny_layers(1)
