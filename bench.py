@@ -264,7 +264,13 @@ def bypass_sweep(ctx, leg, steps):
                     ev[i][1].record()
         group.set_kv_len([Smax + 32])
         w, med, mn = timed(ctx, run, steps, 8)
-        out["eq5" if d < 0 else f"d{d}"] = {"us_median": round(med, 2), "us_min": round(mn, 2)}
+        out["eq5_three_phases" if d < 0 else f"d{d}"] = {"us_median": round(med, 2), "us_min": round(mn, 2)}
+        if d < 0:
+            # the same arithmetic on the six-kernel schedule (QKV, attention, O, gate/up, down, merge one after another)
+            cq.cqil_set_tuning("eq5_fused", 0)
+            w, med, mn = timed(ctx, run, steps, 8)
+            cq.cqil_set_tuning("eq5_fused", 1)
+            out["eq5_six_kernels"] = {"us_median": round(med, 2), "us_min": round(mn, 2)}
     return out
 
 

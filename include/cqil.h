@@ -172,7 +172,9 @@ int cqil_group_forward_static(const cqil_dims *dims, int P, int bypass_d, const 
  * kernels as cqil_group_forward, with HIP events recorded on `stream` around each of them.  Waits for the
  * step to finish and writes the six elapsed times in milliseconds to kernel_ms_out (host, 6 floats), in
  * the order: QKV projection (+norm, rotary, append), attention, O projection, gate/up (+bypass, norm,
- * SwiGLU), down projection, merge of Eq.3 / Eq.4.  Creates and destroys its events; blocks the host. */
+ * SwiGLU), down projection, merge of Eq.3 / Eq.4.  In the fused schedule of bypass_d == -1 (see cqil_set_tuning,
+ * "eq5_fused") slot 0 holds the QKV + gate/up launch, slot 2 the O + down launch, slots 3 and 4 are zero.
+ * Creates and destroys its events; blocks the host. */
 int cqil_decode_step_profile(const cqil_dims *dims, int P, int bypass_d, const void *packed, cqil_kv *kv /* host */,
                              const void *x_in, void *x_out, int B, void *workspace, size_t workspace_bytes,
                              void *stream, float *kernel_ms_out /* host */);
@@ -231,7 +233,10 @@ int cqil_model_forward_substituted(cqil_model *m /* host */, const int32_t *toke
  * token-parallel path: 1 = 256 tokens x 256 weight rows, 2 = 128 x 256 and the tiled kernel also for up to 8 token
  * rows, where the default is a barrier-free streaming kernel; 0 = default).  The k split, the number of K slices and,
  * for up to 8 rows, the choice between the two GEMM kernels change the order in which partial sums are added, nothing
- * else; for more rows the GEMM tile changes no result at all.  Unknown key or bad value: CQIL_EINVAL. */
+ * else; for more rows the GEMM tile changes no result at all.  "eq5_fused" (single-token step of the attention-FFN parallel
+ * form, bypass_d == -1: 1 = default, the step runs as three fused phases -- QKV and gate/up as one shared-input
+ * launch, attention, O and down as one K-concatenated launch -- plus the merge; 0 = the six-kernel schedule of Eq.4;
+ * both give the same result bit for bit).  Unknown key or bad value: CQIL_EINVAL. */
 int cqil_set_tuning(const char *key, int value);
 
 /* Library build information (host-only). */

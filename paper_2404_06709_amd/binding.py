@@ -224,7 +224,7 @@ def cqil_set_tuning(key: str, value: int) -> None:
 
 
 TUNING_DEFAULTS = {"ksplit_qkv": 4, "ksplit_o": 0, "ksplit_gu": 0, "ksplit_d": 0, "down_slice_max": 8192,
-                   "gemm_tile": 0}
+                   "gemm_tile": 0, "eq5_fused": 1}
 
 
 def reset_tuning() -> None:

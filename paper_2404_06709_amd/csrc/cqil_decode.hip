@@ -75,11 +75,10 @@ __device__ __forceinline__ void scale_row_in_lds(float* xs, const T* g, const fl
 //    strips holding rows (e, e + d_k/2), e = 16 tp .. 16 tp + 15, of one head of q, k or v.
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
-    const T* __restrict__ x, const T* __restrict__ wqkv, const T* __restrict__ g_attn, const float2* __restrict__ rope,
-    const int32_t* __restrict__ kv_len, T* __restrict__ kc, T* __restrict__ vc, float* __restrict__ q_out,
-    int d_model, int n_heads, int d_k, int max_seq, int b_max, float eps, int ksplit) {
-    extern __shared__ float smem[];
+__device__ __forceinline__ void qkv_rope_body(
+    float* smem, int block, const T* __restrict__ x, const T* __restrict__ wqkv, const T* __restrict__ g_attn,
+    const float2* __restrict__ rope, const int32_t* __restrict__ kv_len, T* __restrict__ kc, T* __restrict__ vc,
+    float* __restrict__ q_out, int d_model, int n_heads, int d_k, int max_seq, int b_max, float eps, int ksplit) {
     constexpr int KB = tile<T>::KB, TE = tile<T>::kElems;
     float* xs = smem;             // d_model
     float* red = xs + d_model;    // kRedFloats
@@ -92,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     const int units = 3 * n_heads * pairs_per_head;   // per layer
     const int uw = kWaves / ksplit;
     const int ul = w / ksplit, ks = w % ksplit;
-    const int unit = blockIdx.x * uw + ul;
+    const int unit = block * uw + ul;
     const bool on = unit < units;
     const int tp = unit % pairs_per_head;
     const int hu = unit / pairs_per_head;
@@ -157,19 +156,27 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
     }
 }
 
+template <typename T>
+__global__ __launch_bounds__(kThreads) void qkv_rope_kernel(
+    const T* __restrict__ x, const T* __restrict__ wqkv, const T* __restrict__ g_attn, const float2* __restrict__ rope,
+    const int32_t* __restrict__ kv_len, T* __restrict__ kc, T* __restrict__ vc, float* __restrict__ q_out,
+    int d_model, int n_heads, int d_k, int max_seq, int b_max, float eps, int ksplit) {
+    extern __shared__ float smem[];
+    qkv_rope_body<T>(smem, blockIdx.x, x, wqkv, g_attn, rope, kv_len, kc, vc, q_out, d_model, n_heads, d_k, max_seq, b_max,
+                     eps, ksplit);
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // 3. Output projection, per layer: a_l = Wo_l ctx_l.  grid = (unit blocks, P); a unit is one strip of 16 output
 //    rows.  Wo is K-concatenated: the columns of layer l are the tiles l*d_model/KB .. of every strip.
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(kThreads) void oproj_kernel(const float* __restrict__ ctx, const T* __restrict__ wo,
-                                                          float* __restrict__ a, int P, int d_model, int ksplit) {
-    extern __shared__ float smem[];
+__device__ __forceinline__ void oproj_body(float* smem, int l, const float* __restrict__ ctx, const T* __restrict__ wo,
+                                           float* __restrict__ a, int P, int d_model, int ksplit) {
     constexpr int KB = tile<T>::KB, TE = tile<T>::kElems;
     float* xs = smem;
     float* red = xs + d_model;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-    const int l = blockIdx.y;
     const int units = d_model / 16;
     const int uw = kWaves / ksplit;
     const int ul = w / ksplit, ks = w % ksplit;
@@ -194,17 +201,23 @@ __global__ __launch_bounds__(kThreads) void oproj_kernel(const float* __restrict
     if (on && ks == 0 && lane < 16) a[(size_t)l * d_model + 16 * unit + lane] = y[0];
 }
 
+template <typename T>
+__global__ __launch_bounds__(kThreads) void oproj_kernel(const float* __restrict__ ctx, const T* __restrict__ wo,
+                                                          float* __restrict__ a, int P, int d_model, int ksplit) {
+    extern __shared__ float smem[];
+    oproj_body<T>(smem, blockIdx.y, ctx, wo, a, P, d_model, ksplit);
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // 4. Bypass window + FFN RMSNorm + gate/up projection + SwiGLU.  grid = (unit blocks, P); a unit is one packed
 //    block: the strip of 16 gate rows and the strip of the matching 16 up rows.
 //    h_l = x + sum_{j = max(0, l-d)}^{l} a_j   (Eq.4: own attention plus the d preceding layers' outputs)
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ x, const float* __restrict__ a,
-                                                           const T* __restrict__ wgu, const T* __restrict__ g_ffn,
-                                                           float* __restrict__ u, int P, int bypass_d, int d_model,
-                                                           int d_ffn, float eps, int ksplit) {
-    extern __shared__ float smem[];
+__device__ __forceinline__ void gateup_body(float* smem, int block, const T* __restrict__ x, const float* __restrict__ a,
+                                            const T* __restrict__ wgu, const T* __restrict__ g_ffn,
+                                            float* __restrict__ u, int P, int bypass_d, int d_model, int d_ffn,
+                                            float eps, int ksplit) {
     constexpr int KB = tile<T>::KB, TE = tile<T>::kElems;
     float* xs = smem;
     float* red = xs + d_model;
@@ -214,7 +227,7 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
     const int units = d_ffn / kGuBlock;
     const int uw = kWaves / ksplit;
     const int ul = w / ksplit, ks = w % ksplit;
-    const int unit = blockIdx.x * uw + ul;
+    const int unit = block * uw + ul;
     const bool on = unit < units;
     const int nkb = d_model / KB;
     const int per = (nkb + ksplit - 1) / ksplit;
@@ -259,21 +272,47 @@ __global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ 
         u[(size_t)l * d_ffn + unit * kGuBlock + lane] = y[0] / (1.0f + expf(-y[0])) * y[1];
 }
 
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gateup_kernel(const T* __restrict__ x, const float* __restrict__ a,
+                                                           const T* __restrict__ wgu, const T* __restrict__ g_ffn,
+                                                           float* __restrict__ u, int P, int bypass_d, int d_model,
+                                                           int d_ffn, float eps, int ksplit) {
+    extern __shared__ float smem[];
+    gateup_body<T>(smem, blockIdx.x, x, a, wgu, g_ffn, u, P, bypass_d, d_model, d_ffn, eps, ksplit);
+}
+
+// Attention-FFN parallel form (App. A, Eq.5): every feed-forward module reads the shared input itself, so the QKV
+// projection and the gate/up projection are two parts of ONE shared-input, N-concatenated product: one launch, one
+// RMS statistic of x, two sets of gains (g_attn for the q/k/v rows, g_ffn for the gate/up rows).  Workgroups
+// 0 .. q_blocks-1 of a layer take QKV units, the rest gate/up units.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void qkv_gateup_kernel(
+    const T* __restrict__ x, const T* __restrict__ wqkv, const T* __restrict__ g_attn, const float2* __restrict__ rope,
+    const int32_t* __restrict__ kv_len, T* __restrict__ kc, T* __restrict__ vc, float* __restrict__ q_out,
+    const T* __restrict__ wgu, const T* __restrict__ g_ffn, float* __restrict__ u, int P, int d_model, int n_heads,
+    int d_k, int d_ffn, int max_seq, int b_max, float eps, int ksplit_q, int ksplit_g, int q_blocks) {
+    extern __shared__ float smem[];
+    if ((int)blockIdx.x < q_blocks)
+        qkv_rope_body<T>(smem, blockIdx.x, x, wqkv, g_attn, rope, kv_len, kc, vc, q_out, d_model, n_heads, d_k, max_seq,
+                         b_max, eps, ksplit_q);
+    else
+        gateup_body<T>(smem, (int)blockIdx.x - q_blocks, x, nullptr, wgu, g_ffn, u, P, CQIL_ATTN_FFN_PARALLEL, d_model,
+                       d_ffn, eps, ksplit_g);
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // 5. Down projection over the K-concatenated Wdown [d_model][P*d_ffn (+ zero padding)]: the sum over the group's
 //    layers in Eq.3 / Eq.4 is part of the dot product.  grid = (strip blocks, K slices); every slice writes its
 //    partial sums, merge_kernel adds them in slice order (deterministic, no atomics).
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict__ u, const T* __restrict__ wdown,
-                                                         float* __restrict__ part, int K, int Kp, int d_model,
-                                                         int slice_len, int ksplit) {
-    extern __shared__ float smem[];
+__device__ __forceinline__ void down_body(float* smem, int slice, const float* __restrict__ u,
+                                          const T* __restrict__ wdown, float* __restrict__ part, int K, int Kp,
+                                          int d_model, int slice_len, int ksplit) {
     constexpr int KB = tile<T>::KB, TE = tile<T>::kElems;
     float* xs = smem;                 // slice_len
     float* red = xs + slice_len;      // kRedFloats
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-    const int slice = blockIdx.y;
     const int k0 = slice * slice_len;
     const int len = min(slice_len, Kp - k0);  // multiple of KB
     const int uw = kWaves / ksplit;
@@ -298,6 +337,32 @@ __global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict_
     tile_strips_dot<T, 1, kU1>(strips, n_kb, xs + kb0 * KB, wt, y);
     combine_ksplit<1>(y, ksplit, ul, ks, red);
     if (on && ks == 0 && lane < 16) part[(size_t)slice * d_model + 16 * unit + lane] = y[0];
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void down_kernel(const float* __restrict__ u, const T* __restrict__ wdown,
+                                                         float* __restrict__ part, int K, int Kp, int d_model,
+                                                         int slice_len, int ksplit) {
+    extern __shared__ float smem[];
+    down_body<T>(smem, blockIdx.y, u, wdown, part, K, Kp, d_model, slice_len, ksplit);
+}
+
+// Eq.5's second contraction: without bypassing nothing needs a layer's attention output before its feed-forward
+// output, so sum_l Wo_l ctx_l + sum_l Wdown_l u_l is ONE K-concatenated product [Wo_cat | Wdown_cat] [ctx; u]: one
+// launch whose K slices are the P layers' segments of Wo (partial sums = the a_l, kept for the merge) followed by the
+// slices of Wdown.  grid = (strip blocks, P + n_slices); the strip blocks of the two parts may differ in number
+// (different k splits): a workgroup past its part's count has nothing to do.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void oproj_down_kernel(const float* __restrict__ ctx, const T* __restrict__ wo,
+                                                               float* __restrict__ a, const float* __restrict__ u,
+                                                               const T* __restrict__ wdown, float* __restrict__ part,
+                                                               int P, int K, int Kp, int d_model, int slice_len,
+                                                               int ksplit_o, int ksplit_d) {
+    extern __shared__ float smem[];
+    if ((int)blockIdx.y < P)
+        oproj_body<T>(smem, blockIdx.y, ctx, wo, a, P, d_model, ksplit_o);
+    else
+        down_body<T>(smem, (int)blockIdx.y - P, u, wdown, part, K, Kp, d_model, slice_len, ksplit_d);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -338,8 +403,19 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
 
     // optional per-kernel timing: event i is recorded before kernel i, the last event after the last kernel
 #define CQIL_MARK(i) do { if (s.ev) (void)hipEventRecord(s.ev[i], st); } while (0)
+    // Eq.5 (attention-FFN parallel form): three dependent phases instead of five -- QKV + gate/up in one shared-input
+    // launch, attention, O + down in one K-concatenated launch -- then the merge.
+    const bool fused = s.bypass_d < 0 && g_tune.eq5_fused.load() != 0;
+    const int ks_d = t_d ? t_d
+                         : (narrow ? (P >= 4 ? 1 : (P >= 2 ? 2 : 4)) : split_for((long)(dm / 16) * s.wl.n_slices, 16384));
     CQIL_MARK(0);
-    {
+    if (fused) {
+        const int units_q = 3 * nh * (dk / 32), uw_q = kWaves / ks_q, q_blocks = (units_q + uw_q - 1) / uw_q;
+        const int units_g = f / kGuBlock, uw_g = kWaves / ks_g, g_blocks = (units_g + uw_g - 1) / uw_g;
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(qkv_gateup_kernel<T>), dim3(q_blocks + g_blocks, P), dim3(kThreads), lds_x, st,
+                           (const T*)s.x_in, wqkv, g_attn, rope, s.kv_len, (T*)s.kc, (T*)s.vc, q, wgu, g_ffn, u, P, dm, nh,
+                           dk, f, d.max_seq, s.b_max, d.rms_eps, ks_q, ks_g, q_blocks);
+    } else {
         const int units = 3 * nh * (dk / 32), uw = kWaves / ks_q;
         hipLaunchKernelGGL(HIP_KERNEL_NAME(qkv_rope_kernel<T>), dim3((units + uw - 1) / uw, P), dim3(kThreads), lds_x, st,
                            (const T*)s.x_in, wqkv, g_attn, rope, s.kv_len, (T*)s.kc, (T*)s.vc, q, dm, nh, dk,
@@ -360,26 +436,33 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     }
 #undef CQIL_ATTN
     CQIL_MARK(2);
-    {
-        const int units = dm / 16, uw = kWaves / ks_o;
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(oproj_kernel<T>), dim3((units + uw - 1) / uw, P), dim3(kThreads), lds_x, st,
-                           ctx, wo, a, P, dm, ks_o);
-    }
-    CQIL_MARK(3);
-    {
-        const int units = f / kGuBlock, uw = kWaves / ks_g;
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(gateup_kernel<T>), dim3((units + uw - 1) / uw, P), dim3(kThreads), lds_x, st,
-                           (const T*)s.x_in, a, wgu, g_ffn, u, P, bd, dm, f, d.rms_eps, ks_g);
-    }
-    CQIL_MARK(4);
-    {
-        const int ks_d = t_d ? t_d
-                                         : (narrow ? (P >= 4 ? 1 : (P >= 2 ? 2 : 4))
-                                                   : split_for((long)(dm / 16) * s.wl.n_slices, 16384));
-        const int units = dm / 16, uw = kWaves / ks_d;
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(down_kernel<T>), dim3((units + uw - 1) / uw, s.wl.n_slices), dim3(kThreads),
-                           ((size_t)s.wl.down_slice + kRedFloats) * sizeof(float), st, u, wdown, dpart, K, Kp, dm,
-                           s.wl.down_slice, ks_d);
+    if (fused) {
+        const int units = dm / 16, uw_o = kWaves / ks_o, uw_d = kWaves / ks_d;
+        const int blocks = max((units + uw_o - 1) / uw_o, (units + uw_d - 1) / uw_d);
+        const size_t lds = ((size_t)max(dm, s.wl.down_slice) + kRedFloats + 16) * sizeof(float);
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(oproj_down_kernel<T>), dim3(blocks, P + s.wl.n_slices), dim3(kThreads), lds, st,
+                           ctx, wo, a, u, wdown, dpart, P, K, Kp, dm, s.wl.down_slice, ks_o, ks_d);
+        CQIL_MARK(3);
+        CQIL_MARK(4);
+    } else {
+        {
+            const int units = dm / 16, uw = kWaves / ks_o;
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(oproj_kernel<T>), dim3((units + uw - 1) / uw, P), dim3(kThreads), lds_x, st,
+                               ctx, wo, a, P, dm, ks_o);
+        }
+        CQIL_MARK(3);
+        {
+            const int units = f / kGuBlock, uw = kWaves / ks_g;
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(gateup_kernel<T>), dim3((units + uw - 1) / uw, P), dim3(kThreads), lds_x, st,
+                               (const T*)s.x_in, a, wgu, g_ffn, u, P, bd, dm, f, d.rms_eps, ks_g);
+        }
+        CQIL_MARK(4);
+        {
+            const int units = dm / 16, uw = kWaves / ks_d;
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(down_kernel<T>), dim3((units + uw - 1) / uw, s.wl.n_slices), dim3(kThreads),
+                               ((size_t)s.wl.down_slice + kRedFloats) * sizeof(float), st, u, wdown, dpart, K, Kp, dm,
+                               s.wl.down_slice, ks_d);
+        }
     }
     CQIL_MARK(5);
     hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 255) / 256, 1), dim3(256), 0, st, (const T*)s.x_res,

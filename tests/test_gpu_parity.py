@@ -445,6 +445,34 @@ def test_attention_ffn_parallel_form_matches_oracle(shape, P, dtype):
     assert rel_err(synth.widen(y), eq5) <= TOL[dtype] < rel_err(synth.widen(y), eq3)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape,P", [(TINY, 1), (MID, 3), (WIDE, 4)])
+def test_eq5_fused_schedule_matches_oracle_and_the_six_kernel_schedule(shape, P, dtype):
+    """App. A, Eq.5 on the single-token path: the default schedule runs QKV + gate/up as one shared-input launch and
+    O + down as one K-concatenated launch (WIDE at P = 4: four layer segments of Wo and two slices of Wdown).  Against
+    the oracle, and bit for bit against the six-kernel schedule; also with k splits that give the two parts of a
+    fused launch different numbers of workgroups."""
+    d = cq.CQIL_ATTN_FFN_PARALLEL
+    pair = Pair(shape, P, dtype, max_seq=200, b_max=1, seed=5400 + P, w_std=0.05, gain_jitter=0.1)
+    pair.fill_cache([131], seed=19)
+    try:
+        for knobs in ({}, {"ksplit_o": 1, "ksplit_d": 8, "ksplit_qkv": 8, "ksplit_gu": 1},
+                      {"ksplit_o": 8, "ksplit_d": 1, "ksplit_qkv": 1, "ksplit_gu": 8, "down_slice_max": 512}):
+            outs = []
+            for fused in (1, 0):
+                cq.reset_tuning()
+                for kk, vv in knobs.items():
+                    cq.cqil_set_tuning(kk, vv)
+                cq.cqil_set_tuning("eq5_fused", fused)
+                pair.set_lens([131])
+                y, _ = pair.step(pair.hidden(1, 1, seed=5), d, label=f"Eq.5 fused={fused} {knobs} P={P} {dtype}")
+                outs.append((y, pair.group.k[:, 0, :, 131].clone(), pair.group.v[:, 0, :, 131].clone()))
+            assert torch.equal(outs[0][0].view(torch.uint8), outs[1][0].view(torch.uint8))
+            assert torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][2], outs[1][2])
+    finally:
+        cq.reset_tuning()
+
+
 def test_prefill_then_decode_equals_one_prefill():
     """Property that holds at any size: prefilling T tokens equals prefilling T-1 and decoding one."""
     pair = Pair(TINY, 2, torch.float32, max_seq=64, b_max=1, seed=11, w_std=0.05, gain_jitter=0.1)
