@@ -157,7 +157,7 @@ int cqil_group_forward(const cqil_dims *dims, int P, int bypass_d, const void *p
 
 /* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): cqil_group_forward with the workspace in a static device array
- * of cqil_static_scratch_bytes() bytes (4 MiB) that is part of the library's code object; every GPU the library
+ * of cqil_static_scratch_bytes() bytes (8 MiB) that is part of the library's code object; every GPU the library
  * runs on holds its own copy until the process ends.  Same arguments, results and error returns as
  * cqil_group_forward, bit for bit (the same kernels run); a step whose cqil_workspace_bytes() exceeds the array
  * (long prefill chunks, wide batches) is CQIL_ESIZE.  Single-token decode of a 33B-shaped group of up to 16 layers
@@ -229,7 +229,7 @@ int cqil_model_forward_substituted(cqil_model *m /* host */, const int32_t *toke
  * before sizing workspaces).  Keys: "ksplit_qkv", "ksplit_o", "ksplit_gu", "ksplit_d" (waves that share one unit
  * of work and split its k range in the QKV / O / gate-up / down kernel: 1, 2, 4 or 8; 0 = chosen by shape),
  * "down_slice_max" (longest K slice of the down projection, multiple of 512, at
- * most 12288): single-token decode kernels.  "gemm_tile" (workgroup tile of the bf16 matrix-core GEMM of the
+ * most 12288; default 3072): single-token decode kernels.  "gemm_tile" (workgroup tile of the bf16 matrix-core GEMM of the
  * token-parallel path: 1 = 256 tokens x 256 weight rows, 2 = 128 x 256 and the tiled kernel also for up to 8 token
  * rows, where the default is a barrier-free streaming kernel; 0 = default).  The k split, the number of K slices and,
  * for up to 8 rows, the choice between the two GEMM kernels change the order in which partial sums are added, nothing

@@ -223,7 +223,7 @@ def cqil_set_tuning(key: str, value: int) -> None:
         raise CqilError(rc, f"cqil_set_tuning({key}, {value})")
 
 
-TUNING_DEFAULTS = {"ksplit_qkv": 4, "ksplit_o": 0, "ksplit_gu": 0, "ksplit_d": 0, "down_slice_max": 8192,
+TUNING_DEFAULTS = {"ksplit_qkv": 0, "ksplit_o": 0, "ksplit_gu": 0, "ksplit_d": 0, "down_slice_max": 3072,
                    "gemm_tile": 0, "eq5_fused": 1}
 
 

@@ -64,25 +64,30 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
 #pragma unroll
     for (int j = 0; j < V; ++j) acc[j] = 0.f;
     const int n_steps = (S + SPW - 1) / SPW;
-    for (int i0 = w * U; i0 < n_steps; i0 += NW * U) {
-        uint4 kraw[U], vraw[U];
+    // Software pipeline over the wave's iterations (U slot steps each): the K and V loads of iteration i+1 are
+    // requested before iteration i is evaluated, so a wave pays the memory latency once, not once per iteration.
+    // Two register sets, the loop advances two iterations per trip (static register indices).
+    uint4 kraw[2][U], vraw[2][U];
+    auto request = [&](int set, int i0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = (i0 + u) * SPW + sg;
+            kraw[set][u] = s < S ? load16_stream(kb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = (i0 + u) * SPW + sg;
+            vraw[set][u] = s < S ? load16_stream(vb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto evaluate = [&](int set, int i0) __attribute__((always_inline)) {
+        float sc[U], mloc = -INFINITY;
         bool ok[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int s = (i0 + u) * SPW + sg;
-            ok[u] = s < S;
-            kraw[u] = ok[u] ? load16_stream(kb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int s = (i0 + u) * SPW + sg;
-            vraw[u] = ok[u] ? load16_stream(vb + (size_t)s * DK) : make_uint4(0, 0, 0, 0);
-        }
-        float sc[U], mloc = -INFINITY;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
+            ok[u] = (i0 + u) * SPW + sg < S;
             float f[V], dot = 0.f;
-            elem<T>::unpack(kraw[u], f);
+            elem<T>::unpack(kraw[set][u], f);
 #pragma unroll
             for (int j = 0; j < V; ++j) dot = fmaf(f[j], qv[j], dot);
             dot = lane_group_sum<LPS>(dot);
@@ -99,12 +104,23 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
             for (int u = 0; u < U; ++u) {
                 const float p = ok[u] ? __builtin_amdgcn_exp2f(sc[u] - nm) : 0.f;
                 float f[V];
-                elem<T>::unpack(vraw[u], f);
+                elem<T>::unpack(vraw[set][u], f);
                 lsum += p;
 #pragma unroll
                 for (int j = 0; j < V; ++j) acc[j] = fmaf(p, f[j], acc[j]);
             }
             mx = nm;
+        }
+    };
+    constexpr int STRIDE = NW * U;
+    int i0 = w * U;
+    if (i0 < n_steps) request(0, i0);
+    for (; i0 < n_steps; i0 += 2 * STRIDE) {
+        if (i0 + STRIDE < n_steps) request(1, i0 + STRIDE);
+        evaluate(0, i0);
+        if (i0 + STRIDE < n_steps) {
+            if (i0 + 2 * STRIDE < n_steps) request(0, i0 + 2 * STRIDE);
+            evaluate(1, i0 + STRIDE);
         }
     }
     // merge the slot groups of the wave, then the waves
@@ -142,40 +158,45 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
     }
 }
 
-// Merge of Eq.3 / Eq.4 for M token rows: x_out = x + sum_i a_i + sum of the K-slice partials of the down
-// projection, added in slice order; also advances the cache lengths.  grid = (ceil(d_model/256), M).
-//   a [P][M][d_model] fp32, part [n_slices][M][d_model] fp32
+// Merge of Eq.3 / Eq.4 for one token row: x_out = x + sum_i a_i + sum of the K-slice partials of the down projection;
+// also advances the cache lengths.  grid = ceil(d_model / 64) workgroups of 64 x kMergeY threads: thread (tx, ty) adds
+// the terms ty, ty + kMergeY, ... of the list [a_0 .. a_{P-1}, part_0 .. part_{n_slices-1}] for output element tx (all
+// its loads are requested before the first add), the kMergeY partial sums meet in LDS and are added to x in ty order:
+// a fixed order, and one memory latency instead of one per batch of terms.
+//   a [P][d_model] fp32, part [n_slices][d_model] fp32
+constexpr int kMergeY = 8, kMergeTerms = 8;   // up to kMergeY * kMergeTerms = 64 terms in one pass
 template <typename T>
-__global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ x, const float* __restrict__ a,
-                                                    const float* __restrict__ part, T* __restrict__ x_out,
-                                                    int32_t* __restrict__ kv_len, int advance, int P, int n_slices,
-                                                    int M, int d_model, int B, int T_new) {
-    const int o = blockIdx.x * 256 + threadIdx.x;
-    const int m = blockIdx.y;
+__global__ __launch_bounds__(64 * kMergeY) void merge_kernel(const T* __restrict__ x, const float* __restrict__ a,
+                                                             const float* __restrict__ part, T* __restrict__ x_out,
+                                                             int32_t* __restrict__ kv_len, int advance, int P,
+                                                             int n_slices, int d_model, int B, int T_new) {
+    __shared__ float sums[kMergeY][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int o = blockIdx.x * 64 + tx;
+    const int n_terms = P + n_slices;
+    float s = 0.f;
     if (o < d_model) {
-        const size_t idx = (size_t)m * d_model + o;
-        // the terms are added in a fixed order (x, layers, slices); loads are issued eight at a time so that the
-        // kernel waits for memory a few times, not once per term
-        float v = elem<T>::load(x + idx);
-        const size_t stride = (size_t)M * d_model;
-        for (int j0 = 0; j0 < P; j0 += 8) {
-            float t[8];
+        for (int t0 = ty; t0 < n_terms; t0 += kMergeY * kMergeTerms) {
+            float t[kMergeTerms];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) t[u] = (j0 + u < P) ? a[(size_t)(j0 + u) * stride + idx] : 0.f;
+            for (int u = 0; u < kMergeTerms; ++u) {
+                const int j = t0 + u * kMergeY;
+                t[u] = j < P ? a[(size_t)j * d_model + o] : (j < n_terms ? part[(size_t)(j - P) * d_model + o] : 0.f);
+            }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v += t[u];
+            for (int u = 0; u < kMergeTerms; ++u) s += t[u];
         }
-        for (int s0 = 0; s0 < n_slices; s0 += 8) {
-            float t[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) t[u] = (s0 + u < n_slices) ? part[(size_t)(s0 + u) * stride + idx] : 0.f;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v += t[u];
-        }
-        elem<T>::store(x_out + idx, v);
     }
-    if (advance && m == 0 && blockIdx.x == 0)
-        for (int b = threadIdx.x; b < B; b += 256) kv_len[b] += T_new;
+    sums[ty][tx] = s;
+    __syncthreads();
+    if (ty == 0 && o < d_model) {
+        float v = elem<T>::load(x + o);
+#pragma unroll
+        for (int y = 0; y < kMergeY; ++y) v += sums[y][tx];
+        elem<T>::store(x_out + o, v);
+    }
+    if (advance && blockIdx.x == 0)
+        for (int b = threadIdx.x; b < B; b += 64 * kMergeY) kv_len[b] += T_new;
 }
 
 }  // namespace cqil

@@ -397,7 +397,7 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     const int t_q = g_tune.ksplit_qkv.load(), t_o = g_tune.ksplit_o.load(), t_g = g_tune.ksplit_gu.load(),
               t_d = g_tune.ksplit_d.load();
     const int ks_q = t_q ? t_q : split_for(3L * nh * (dk / 32) * P, 6144);
-    const int ks_o = t_o ? t_o : (narrow ? (P >= 4 ? 4 : 8) : (P >= 4 ? 1 : (P >= 2 ? 2 : 4)));
+    const int ks_o = t_o ? t_o : ((narrow && P >= 4) ? 4 : 8);
     const int ks_g = t_g ? t_g : (narrow ? ((P == 2 || P == 3) ? 4 : 2) : split_for((long)(f / kGuBlock) * P, 16384));
     const size_t lds_x = ((size_t)dm + kRedFloats + 16) * sizeof(float);
 
@@ -406,8 +406,7 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
     // Eq.5 (attention-FFN parallel form): three dependent phases instead of five -- QKV + gate/up in one shared-input
     // launch, attention, O + down in one K-concatenated launch -- then the merge.
     const bool fused = s.bypass_d < 0 && g_tune.eq5_fused.load() != 0;
-    const int ks_d = t_d ? t_d
-                         : (narrow ? (P >= 4 ? 1 : (P >= 2 ? 2 : 4)) : split_for((long)(dm / 16) * s.wl.n_slices, 16384));
+    const int ks_d = t_d ? t_d : 8;
     CQIL_MARK(0);
     if (fused) {
         const int units_q = 3 * nh * (dk / 32), uw_q = kWaves / ks_q, q_blocks = (units_q + uw_q - 1) / uw_q;
@@ -465,8 +464,8 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
         }
     }
     CQIL_MARK(5);
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 255) / 256, 1), dim3(256), 0, st, (const T*)s.x_res,
-                       a, dpart, (T*)s.x_out, s.kv_len, s.advance, P, s.wl.n_slices, 1, dm, 1, 1);
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(merge_kernel<T>), dim3((dm + 63) / 64), dim3(64 * kMergeY), 0, st,
+                       (const T*)s.x_res, a, dpart, (T*)s.x_out, s.kv_len, s.advance, P, s.wl.n_slices, dm, 1, 1);
     CQIL_MARK(6);
 #undef CQIL_MARK
     return hipGetLastError();

@@ -95,7 +95,7 @@ static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 // Workspace of cqil_group_forward_static: one array per GPU, part of the loaded code object, held until the process
 // ends.  Host code never passes the array's name to a kernel (on the host the name is only a handle of the symbol):
 // the device address is looked up once per device and kept.
-constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
 constexpr int kMaxDevices = 64;
 static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
 static std::mutex g_scratch_mu;

@@ -24,7 +24,7 @@ constexpr int kMaxP = 16;
 // Atomics: a knob may be set while another thread launches (each launch reads a knob once; a step sized with one
 // value of down_slice_max and launched with another is caught by the workspace-size check or runs with the new one).
 struct Tuning {
-    std::atomic<int> ksplit_qkv{4}, ksplit_o{0}, ksplit_gu{0}, ksplit_d{0}, down_slice_max{8192};  // 0 = by shape
+    std::atomic<int> ksplit_qkv{0}, ksplit_o{0}, ksplit_gu{0}, ksplit_d{0}, down_slice_max{3072};  // 0 = by shape
     std::atomic<int> gemm_tile{0};
     std::atomic<int> eq5_fused{1};  // single-token Eq.5 step: 1 = three fused phases, 0 = the six-kernel schedule
 };

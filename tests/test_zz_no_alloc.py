@@ -39,7 +39,7 @@ def _both(pair, x, d, lens):
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_static_scratch_entry_point_matches_group_forward(dtype):
-    assert cq.cqil_static_scratch_bytes() == 4 << 20
+    assert cq.cqil_static_scratch_bytes() == 8 << 20
     pair = Pair(MID, 3, dtype, max_seq=96, b_max=3, seed=4100, w_std=0.05, gain_jitter=0.1)
     pair.fill_cache([40, 0, 17], seed=3)
     lens = [40, 0, 17]
