@@ -490,10 +490,25 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
                        dm, d.rms_eps);
     hipError_t ge;
     float* part = s.wl.gemm_part_floats ? (float*)(s.ws + s.wl.gemm_part) : nullptr;
-    if ((ge = gemm_any<T, T, false>(nrm, wqkv, qkv, nullptr, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm,
-                            (size_t)3 * dm, 0, (size_t)3 * dm, st, part, s.wl.gemm_part_floats)) != hipSuccess) return ge;
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M), dim3(row_threads), 0, st,
-                       qkv, rope, s.kv_len, (T*)s.kc, (T*)s.vc, P, s.T, nh, dk, d.max_seq, s.b_max);
+    // Prefill-sized bf16 products of the LLaMA head sizes: the rotary embedding and the KV append run in the epilogue
+    // of the QKV product (q goes to the QKV rows, k and v straight into the caches); otherwise a separate pass.
+    bool rope_fused = false;
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        if (M >= 512 && dm % 256 == 0 && (dk == 64 || dk == 128) && g_tune.gemm_tile.load() == 0) {
+            GemmRope rp;
+            rp.rope = rope; rp.kv_len = s.kv_len; rp.kc = (bf16_t*)s.kc; rp.vc = (bf16_t*)s.vc;
+            rp.T_new = s.T; rp.n_heads = nh; rp.d_k = dk; rp.max_seq = d.max_seq; rp.b_max = s.b_max; rp.d_model = dm;
+            if ((ge = gemm_mfma_qkv_rope(nrm, wqkv, qkv, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm, (size_t)3 * dm,
+                                         (size_t)3 * dm, rp, st)) != hipSuccess) return ge;
+            rope_fused = true;
+        }
+    }
+    if (!rope_fused) {
+        if ((ge = gemm_any<T, T, false>(nrm, wqkv, qkv, nullptr, M, 3 * dm, dm, dm, dm, (size_t)P * 3 * dm, P, Mdm,
+                                (size_t)3 * dm, 0, (size_t)3 * dm, st, part, s.wl.gemm_part_floats)) != hipSuccess) return ge;
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(rope_append_kernel<T>), dim3(M), dim3(row_threads), 0, st,
+                           qkv, rope, s.kv_len, (T*)s.kc, (T*)s.vc, P, s.T, nh, dk, d.max_seq, s.b_max);
+    }
     const int lps = dk * (int)sizeof(T) / 16;
     bool attn_done = false;
     if (s.T == 1) {

@@ -33,8 +33,20 @@ typedef uint32_t gemm_u32x4 __attribute__((ext_vector_type(4)));
 // checks that no offset reaches that range.  Word 3: 32-bit data format, no swizzle (the gfx9 / CDNA encoding).
 constexpr uint32_t kGemmBufRange = 0x80000000u, kGemmBufFlags = 0x00020000u;
 
-// epilogues: plain store, + fp32 residual R[m][n], or SwiGLU over block-interleaved gate / up rows
-constexpr int kEpiNone = 0, kEpiAddR = 1, kEpiSwiglu = 2;
+// epilogues: plain store, + fp32 residual R[m][n], SwiGLU over block-interleaved gate / up rows, or the rotary
+// embedding of the QKV product with the KV-cache append
+constexpr int kEpiNone = 0, kEpiAddR = 1, kEpiSwiglu = 2, kEpiRope = 3;
+
+// Arguments of the kEpiRope epilogue (QKV product of one layer per group z, rows [q | k | v] of d_model each):
+// q is rotated and stored to C, k is rotated and appended to the layer's K cache, v is appended to its V cache, at
+// position kv_len[b] + t of token row m = b * T_new + t.  Requires d_model % 256 == 0 (a workgroup tile lies inside
+// one of q, k, v) and head_dim 64 or 128 (a rotary pair meets in one lane, see RMAP).
+struct GemmRope {
+    const float2* rope;      // [max_seq][head_dim / 2] (cos, sin)
+    const int32_t* kv_len;   // [b_max]
+    bf16_t *kc, *vc;         // [groups][b_max][n_heads][max_seq][head_dim]
+    int T_new, n_heads, d_k, max_seq, b_max, d_model;
+};
 
 __device__ __forceinline__ void gemm_store4(bf16_t* p, const float (&v)[4]) {
     uint2 o;
@@ -49,11 +61,14 @@ __device__ __forceinline__ void gemm_store4(float* p, const float (&v)[4]) {
 // N, K: logical sizes of this group's product; N % 4 == 0, K % 8 == 0, M >= 1.  strip_step / ktile_step: group
 // strides in 16-row strips / 32-column tiles inside W.  R (kEpiAddR): fp32 [M][N] added to the result.
 // kEpiSwiglu: N % 32 == 0 rows as blocks of 16 gate + 16 up rows; C gets N / 2 columns per group.
-template <typename CT, int EPI, int WM, int WN, int TT, bool WSTREAM>
+// RMAP = 1 (head_dim 128 with kEpiRope): the wave's two 32-row fragments are rows e .. e + 31 and e + 64 .. e + 95
+// of one head (e = 0 or 32), so that the rotary pair (e, e + 64) sits in the same lane and register of the two
+// accumulator tiles; RMAP = 0: rows 64 wn .. 64 wn + 63 (for head_dim 64 that already pairs e with e + 32).
+template <typename CT, int EPI, int WM, int WN, int TT, bool WSTREAM, int RMAP = 0>
 __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, CT* __restrict__ C, const float* __restrict__ R, int M,
     int N, int K, size_t lda, size_t Kp, size_t ldc, int groups, size_t sA, size_t strip_step, size_t ktile_step,
-    size_t sC, int ksplit, float* __restrict__ part) {
+    size_t sC, int ksplit, float* __restrict__ part, GemmRope rp) {
     constexpr int BM = 32 * TT * WM, BN = 64 * WN, NT = 64 * WM * WN;
     constexpr int TE = 512;            // elements per tile
     constexpr int STAGE = BM * 64;     // activation elements per LDS stage
@@ -98,7 +113,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
     uint32_t wvo[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-        const int rel = min(4 * wn + 2 * s + (fi >> 4), n_strips - 1 - n0 / 16);
+        const int row_base = RMAP ? 128 * (wn >> 1) + 32 * (wn & 1) + 64 * s : 64 * wn + 32 * s;  // of the tile's 256
+        const int rel = min(row_base / 16 + (fi >> 4), n_strips - 1 - n0 / 16);
         wvo[s] = (uint32_t)(((size_t)rel * w_tiles_per_strip * TE + (fgg * 16 + (fi & 15)) * 8) * 2);
     }
     // WSTREAM: a single band of token tiles reads every weight once: streaming (non-temporal) loads
@@ -263,6 +279,50 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_mfma_kernel(
                     *reinterpret_cast<float4*>(pz + (size_t)m * N + n) =
                         make_float4(acc[t][s][4 * q], acc[t][s][4 * q + 1], acc[t][s][4 * q + 2], acc[t][s][4 * q + 3]);
                 }
+        }
+        return;
+    }
+    if constexpr (EPI == kEpiRope) {
+        // fragment 0 holds rows e .. e + 31 of the first half of a head, fragment 1 the partner rows e + d_k / 2
+        const int half = rp.d_k >> 1;
+        const int nb0 = n0 + (RMAP ? 128 * (wn >> 1) + 32 * (wn & 1) : 64 * wn);  // first row of fragment 0
+        if (nb0 >= N) return;
+        const int sec = nb0 / rp.d_model, nn = nb0 % rp.d_model;  // 0 = q, 1 = k, 2 = v (uniform for the wave)
+        const int h = nn / rp.d_k, e0 = nn % rp.d_k;
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            const int m = m0 + 32 * TT * wm + 32 * t + fi;
+            if (m >= M) continue;
+            const int b = m / rp.T_new, pos = rp.kv_len[b] + m % rp.T_new;
+            const bool pos_ok = pos >= 0 && pos < rp.max_seq;
+            bf16_t* dst;
+            if (sec == 0) {
+                dst = reinterpret_cast<bf16_t*>(C) + (size_t)m * ldc + nb0;
+            } else {
+                if (!pos_ok) continue;
+                dst = (sec == 1 ? rp.kc : rp.vc) +
+                      ((((size_t)z * rp.b_max + b) * rp.n_heads + h) * (size_t)rp.max_seq + pos) * rp.d_k + e0;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int e = 8 * q + 4 * fgg;   // offset inside the fragment: pair index e0 + e .. + 3
+                float lo[4], hi[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { lo[i] = acc[t][0][4 * q + i]; hi[i] = acc[t][1][4 * q + i]; }
+                if (sec < 2 && pos_ok) {
+                    const float4* cs = reinterpret_cast<const float4*>(rp.rope + (size_t)pos * half + e0 + e);
+                    const float4 c01 = cs[0], c23 = cs[1];
+                    const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float a = lo[i], bb = hi[i];
+                        lo[i] = a * co[i] - bb * si[i];
+                        hi[i] = bb * co[i] + a * si[i];
+                    }
+                }
+                gemm_store4(dst + e, lo);
+                gemm_store4(dst + e + half, hi);
+            }
         }
         return;
     }
@@ -516,17 +576,41 @@ static hipError_t gemm_mfma_launch(const bf16_t* A, const bf16_t* W, CT* C, cons
     if (ny == 1)
         hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, EPI, WM, WN, TT, true>), dim3((unsigned)wgs),
                            dim3(64 * WM * WN), lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16,
-                           k_step / 32, sC, ksplit, part);
+                           k_step / 32, sC, ksplit, part, GemmRope{});
     else
         hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<CT, EPI, WM, WN, TT, false>), dim3((unsigned)wgs),
                            dim3(64 * WM * WN), lds_bytes, st, A, W, C, R, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16,
-                           k_step / 32, sC, ksplit, part);
+                           k_step / 32, sC, ksplit, part, GemmRope{});
     if (ksplit > 1) {
         const size_t total = (size_t)groups * M * N / 4;
         const unsigned g = (unsigned)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
         hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_reduce_kernel<CT, EPI>), dim3(g), dim3(256), 0, st, part, C, R, M, N, ldc,
                            groups, sC, ksplit);
     }
+    return hipSuccess;
+}
+
+// QKV product with the rotary embedding and the KV append in the epilogue (see GemmRope): M > 32 token rows, no
+// split along K, 128 x 256 tiles.  A [groups][M][K] (sA apart), W rows [q | k | v] of each group n_step apart.
+static hipError_t gemm_mfma_qkv_rope(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int N, int K, size_t lda, size_t Kp,
+                                     size_t ldc, int groups, size_t sA, size_t n_step, size_t sC, const GemmRope& rp,
+                                     hipStream_t st) {
+    if (M <= 32 || (N & 255) || (K & 7) || K < 8 || rp.d_model % 256 || N != 3 * rp.d_model ||
+        (rp.d_k != 64 && rp.d_k != 128))
+        return hipErrorInvalidValue;
+    if (Kp >= (1u << 21) || lda >= (1u << 21)) return hipErrorInvalidValue;
+    constexpr int BM = 128, BN = 256, SN = 8, SM = 8;
+    const int nx = (N + BN - 1) / BN, ny = (M + BM - 1) / BM;
+    const long supers = (long)groups * ((nx + SN - 1) / SN) * ((ny + SM - 1) / SM);
+    const long wgs = (supers + 7) / 8 * 8 * SM * SN;
+    if (wgs > 0x7fffffffL) return hipErrorInvalidValue;
+    constexpr size_t lds_bytes = 2 * (size_t)BM * 64 * 2;
+    if (rp.d_k == 128)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<bf16_t, kEpiRope, 1, 4, 4, false, 1>), dim3((unsigned)wgs), dim3(256),
+                           lds_bytes, st, A, W, C, nullptr, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16, 0, sC, 1, nullptr, rp);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(gemm_mfma_kernel<bf16_t, kEpiRope, 1, 4, 4, false, 0>), dim3((unsigned)wgs), dim3(256),
+                           lds_bytes, st, A, W, C, nullptr, M, N, K, lda, Kp, ldc, groups, sA, n_step / 16, 0, sC, 1, nullptr, rp);
     return hipSuccess;
 }
 

@@ -375,11 +375,14 @@ def test_small_hidden_states_let_the_branches_dominate(shape, P, dtype):
 
 # ------------------------------------------------------------------------------------------ prefill / batch
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("shape", [MID, ODD])
+@pytest.mark.parametrize("shape", [MID, ODD, TINY])
 def test_prefill_over_several_query_blocks_and_ragged_caches(shape, dtype):
     """Chunks of 300 tokens onto caches of 0 and 70 tokens: three 128-query blocks per head (the last ragged),
     waves whose first query lies beyond several unmasked key tiles, the longest-first block order, and a
-    non-empty cache under several query blocks; head sizes 128 (MID) and 64 (ODD).  Every position is compared."""
+    non-empty cache under several query blocks; head sizes 128 (MID) and 64 (ODD, TINY).  600 token rows: for bf16
+    MID and TINY (widths that are multiples of 256) the rotary embedding and the KV append run in the epilogue of the
+    QKV product, with both row-to-wave maps (head sizes 128 and 64); ODD keeps the separate pass.  Every position
+    is compared."""
     pair = Pair(shape, 2, dtype, max_seq=400, b_max=2, seed=3400, w_std=0.05, gain_jitter=0.1)
     pair.fill_cache([0, 70], seed=24)
     pair.step(pair.hidden(2, 300, seed=1), 1, label=f"prefill 2 x 300 {dtype}")
