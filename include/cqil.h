@@ -233,7 +233,9 @@ int cqil_model_forward_substituted(cqil_model *m /* host */, const int32_t *toke
  * token-parallel path: 1 = 256 tokens x 256 weight rows, 2 = 128 x 256 and the tiled kernel also for up to 8 token
  * rows, where the default is a barrier-free streaming kernel; 0 = default).  The k split, the number of K slices and,
  * for up to 8 rows, the choice between the two GEMM kernels change the order in which partial sums are added, nothing
- * else; for more rows the GEMM tile changes no result at all.  "eq5_fused" (single-token step of the attention-FFN parallel
+ * else; for more rows the GEMM tile changes no result at all.  "attn_prefill" (matrix-core attention of bf16 prefill chunks: 0 = default, the kernel built on 32x32x16
+ * instructions; 1 = the kernel built on 16x16x32 instructions; same arithmetic, different order of partial sums).
+ * "eq5_fused" (single-token step of the attention-FFN parallel
  * form, bypass_d == -1: 1 = default, the step runs as three fused phases -- QKV and gate/up as one shared-input
  * launch, attention, O and down as one K-concatenated launch -- plus the merge; 0 = the six-kernel schedule of Eq.4;
  * both give the same result bit for bit).  Unknown key or bad value: CQIL_EINVAL. */

@@ -224,7 +224,7 @@ def cqil_set_tuning(key: str, value: int) -> None:
 
 
 TUNING_DEFAULTS = {"ksplit_qkv": 0, "ksplit_o": 0, "ksplit_gu": 0, "ksplit_d": 0, "down_slice_max": 3072,
-                   "gemm_tile": 0, "eq5_fused": 1}
+                   "gemm_tile": 0, "eq5_fused": 1, "attn_prefill": 0}
 
 
 def reset_tuning() -> None:

@@ -155,6 +155,9 @@ int cqil_set_tuning(const char* key, int value) {
     } else if (!strcmp(key, "gemm_tile")) {
         if (value < 0 || value > 2) return CQIL_EINVAL;
         g_tune.gemm_tile = value;
+    } else if (!strcmp(key, "attn_prefill")) {
+        if (value < 0 || value > 1) return CQIL_EINVAL;
+        g_tune.attn_prefill = value;
     } else if (!strcmp(key, "eq5_fused")) {
         if (value < 0 || value > 1) return CQIL_EINVAL;
         g_tune.eq5_fused = value;

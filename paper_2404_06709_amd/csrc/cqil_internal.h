@@ -26,6 +26,7 @@ constexpr int kMaxP = 16;
 struct Tuning {
     std::atomic<int> ksplit_qkv{0}, ksplit_o{0}, ksplit_gu{0}, ksplit_d{0}, down_slice_max{3072};  // 0 = by shape
     std::atomic<int> gemm_tile{0};
+    std::atomic<int> attn_prefill{0};  // matrix-core prefill attention: 0 = 32x32x16 instructions, 1 = 16x16x32
     std::atomic<int> eq5_fused{1};  // single-token Eq.5 step: 1 = three fused phases, 0 = the six-kernel schedule
 };
 extern Tuning g_tune;

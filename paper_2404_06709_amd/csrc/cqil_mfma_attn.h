@@ -290,4 +290,254 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// The same computation on v_mfma_f32_32x32x16_bf16 (the form that sustains the full matrix rate on gfx950; the
+// 16x16x32 form above runs at half of it).  Transposed formulation again:
+//   S^T[key][query] = K Q^T     A operand = K rows (lane (i, gg): key i of a 32-key tile, d = 16 ks + 8 gg ..),
+//                               B operand = Q rows (lane (j, gg): query j)
+//   O^T[d][query]   = V^T P^T   A operand = V^T,  B operand = P^T
+// A result lane (j, hf) holds rows 8 q + 4 hf + e (register 4 q + e) of column j: 16 keys of one query per 32-key
+// tile.  Registers 8 h2 .. 8 h2 + 7 are exactly one B-operand fragment of the second product if the 16 key slots
+// (gg, e8) of slab (it, h2) are taken to mean key 32 it + 16 h2 + 8 (e8 >> 2) + 4 gg + (e8 & 3); V^T is staged in
+// LDS in that key order, so P never leaves its registers.  The 32 rows of a V^T tile are the d values in the order
+// i = 8 (d % 4) + (d / 4) % 8: the four pieces a thread writes after transposing its 8 keys x 4 d block then fall
+// next to the pieces of its neighbours (conflict-free 16-byte writes), and a result lane ends up with four
+// consecutive d per register quad.  A wave owns 32 queries; its softmax statistics live in the two lanes (j, 0) and
+// (j, 1): one cross-lane step.  The accumulator is rescaled only when some query's running maximum moved.
+// Workgroup: 4 waves = 128 queries, key tiles of 64, two LDS stages (16 KiB of K, 16 KiB of V^T each for d_k 128).
+// ---------------------------------------------------------------------------------------------------------
+typedef float attn_f32x16 __attribute__((ext_vector_type(16)));
+
+template <int DK>
+__global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma32_kernel(
+    const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+    const int32_t* __restrict__ kv_len, bf16_t* __restrict__ ctx, int P, int B, int T_new, int n_heads, int max_seq,
+    int b_max) {
+    constexpr int NKS = DK / 16;  // k steps of the first product (16 d each)
+    constexpr int NDT = DK / 32;  // 32-row d tiles of the second product
+    constexpr int PPK = DK / 8;   // 16-byte pieces per key row
+    constexpr int TE = 512;       // elements per 1 KiB operand tile (64 pieces)
+    constexpr int KPT = (kPfBKV * PPK) / kPfThreads;        // K pieces per thread and tile
+    constexpr int NVG = (kPfBKV / 8) * (DK / 4);            // V groups (8 keys x 4 d) of a tile
+    static_assert(KPT >= 1 && NVG <= kPfThreads && NVG % 64 == 0, "tile does not fit the workgroup");
+    constexpr int KSZ = 2 * NKS * TE, VSZ = NDT * 4 * TE;
+    __shared__ __align__(16) bf16_t Ks2[2 * KSZ];   // two stages of [32-key tile 0..1][k step]
+    __shared__ __align__(16) bf16_t Vs2[2 * VSZ];   // two stages of [d tile][16-key slab 0..3]
+
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int j = lane & 31, hf = lane >> 5;
+    // workgroup -> (head unit, query block): see the kernel above (a unit's blocks stay on one XCD, longest first)
+    const int nqb = (T_new + kPfBQ - 1) / kPfBQ, units = P * B * n_heads;
+    const int xcd = blockIdx.x & 7, slot_id = blockIdx.x >> 3;
+    const int grp = slot_id / (kPfUnitGroup * nqb), i_in = slot_id % (kPfUnitGroup * nqb);
+    const int qb = nqb - 1 - i_in / kPfUnitGroup;
+    const int unit = xcd + 8 * (grp * kPfUnitGroup + i_in % kPfUnitGroup);
+    if (unit >= units) return;  // padding of the grid (whole workgroup)
+    const int h = unit % n_heads;
+    const int lb = unit / n_heads;
+    const int b = lb % B, l = lb / B;
+    const int M = B * T_new;
+    const size_t d_model = (size_t)n_heads * DK;
+    const int S_b = kv_len[b];
+    const int q0 = qb * kPfBQ + 32 * w;
+    int kv_end = S_b + min(qb * kPfBQ + kPfBQ, T_new);
+    if (kv_end > max_seq) kv_end = max_seq;
+    if (kv_end < 1) return;  // a negative kv_len: nothing to read (whole workgroup)
+    const size_t head_off = ((((size_t)l * b_max + b) * n_heads + h) * (size_t)max_seq) * DK;
+    const bf16_t* kg = kc + head_off;
+    const bf16_t* vg = vc + head_off;
+
+    // Q fragments (B operand): lane (j, hf) holds Q[query j][16 ks + 8 hf ..]
+    uint4 qf[NKS];
+    const int tq = q0 + j;
+    const int qpos = (tq < T_new) ? S_b + tq : -1;  // -1: no such query, every key masked
+    {
+        const bf16_t* qp = qkv + ((size_t)b * T_new + min(tq, T_new - 1)) * (size_t)P * 3 * d_model + (size_t)l * 3 * d_model +
+                           (size_t)h * DK + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+            qf[ks] = (tq < T_new) ? *reinterpret_cast<const uint4*>(qp + 16 * ks) : make_uint4(0, 0, 0, 0);
+    }
+
+    // ---- staging roles.  K: piece p = tid + 256 q -> key p / PPK, piece c = p % PPK of the row (k step c >> 1,
+    // half c & 1); inside its tile the piece goes to slot (key + c) mod 32 of its half, so that the pieces of one
+    // row, which neighbouring threads write, fall into different banks.
+    // V: group v = tid -> d quad dq = v % (DK/4), key group kgp = v / (DK/4): slab kgp >> 1, half gg = kgp & 1,
+    // keys 16 slab + 8 (e8 >> 2) + 4 gg + (e8 & 3).
+    u32x4 kreg[KPT];
+    uint2 vreg[8];
+    const bool v_on = tid < NVG;
+    const int v_dq = tid % (DK / 4), v_kgp = (tid / (DK / 4)) & 7;
+    auto fetch = [&](int key0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < KPT; ++q) {
+            const int p = tid + kPfThreads * q;
+            const int slot = min(key0 + p / PPK, kv_end - 1);  // rows past the end: any row, they are masked
+            kreg[q] = *reinterpret_cast<const u32x4*>(kg + (size_t)slot * DK + 8 * (p % PPK));
+        }
+        if (v_on) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int key = 16 * (v_kgp >> 1) + 8 * (e >> 2) + 4 * (v_kgp & 1) + (e & 3);
+                const int slot = key0 + key;
+                // V rows past the end must be zero: their probabilities are zero, but 0 * garbage may be NaN
+                const uint2 raw = *reinterpret_cast<const uint2*>(vg + (size_t)min(slot, kv_end - 1) * DK + 4 * v_dq);
+                const uint32_t keep = slot < kv_end ? 0xffffffffu : 0u;
+                vreg[e] = make_uint2(raw.x & keep, raw.y & keep);
+            }
+        }
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+        bf16_t* Ks = Ks2 + buf * KSZ;
+        bf16_t* Vs = Vs2 + buf * VSZ;
+#pragma unroll
+        for (int q = 0; q < KPT; ++q) {
+            const int p = tid + kPfThreads * q;
+            const int key = p / PPK, c = p % PPK;
+            const int it = key >> 5, i = key & 31, ks = c >> 1, gg = c & 1;
+            *reinterpret_cast<u32x4*>(Ks + (it * NKS + ks) * TE + (gg * 32 + ((i + c) & 31)) * 8) = kreg[q];
+        }
+        if (v_on) {
+            const int slab = v_kgp >> 1, gg = v_kgp & 1, dt = v_dq >> 3;
+#pragma unroll
+            for (int dd = 0; dd < 4; ++dd) {
+                // piece of d = 4 dq + dd: the 8 keys' values, two per dword
+                const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
+                uint4 o;
+                if (dd < 2) {
+                    o.x = __builtin_amdgcn_perm(vreg[1].x, vreg[0].x, sel);
+                    o.y = __builtin_amdgcn_perm(vreg[3].x, vreg[2].x, sel);
+                    o.z = __builtin_amdgcn_perm(vreg[5].x, vreg[4].x, sel);
+                    o.w = __builtin_amdgcn_perm(vreg[7].x, vreg[6].x, sel);
+                } else {
+                    o.x = __builtin_amdgcn_perm(vreg[1].y, vreg[0].y, sel);
+                    o.y = __builtin_amdgcn_perm(vreg[3].y, vreg[2].y, sel);
+                    o.z = __builtin_amdgcn_perm(vreg[5].y, vreg[4].y, sel);
+                    o.w = __builtin_amdgcn_perm(vreg[7].y, vreg[6].y, sel);
+                }
+                const int i = 8 * dd + (v_dq & 7);  // row of d = 4 dq + dd inside its 32-d tile
+                *reinterpret_cast<uint4*>(Vs + (dt * 4 + slab) * TE + (gg * 32 + i) * 8) = o;
+            }
+        }
+    };
+
+    // first query position of the wave (queries past T_new are not stored: they go unmasked and do not count)
+    int qmin = qpos < 0 ? 0x7fffffff : qpos;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) qmin = min(qmin, __shfl_xor(qmin, off, kWave));
+    qmin = __builtin_amdgcn_readfirstlane(qmin);
+
+    attn_f32x16 acc[NDT];
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
+    float mrun = -INFINITY, lrun = 0.f;
+    const float scale2 = 1.4426950408889634f / sqrtf((float)DK);  // scores in units of log 2: exp(x) = exp2(x log2 e)
+
+    fetch(0);
+    stage(0);
+    fetch(kPfBKV);  // unconditional: rows past the end are clamped (K) or zero (V)
+    __syncthreads();
+    for (int key0 = 0, it_tile = 0; key0 < kv_end; key0 += kPfBKV, ++it_tile) {
+        const bf16_t* Ks = Ks2 + (it_tile & 1) * KSZ;
+        const bf16_t* Vs = Vs2 + (it_tile & 1) * VSZ;
+
+        // ---- S^T = K Q^T for two 32-key tiles
+        attn_f32x16 s[2];
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[it][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                const uint4 kf = *reinterpret_cast<const uint4*>(Ks + (it * NKS + ks) * TE + (hf * 32 + ((j + 2 * ks + hf) & 31)) * 8);
+                s[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(attn_bf16x8, kf),
+                                                                __builtin_bit_cast(attn_bf16x8, qf[ks]), s[it], 0, 0, 0);
+            }
+        }
+        // the other stage was last read before the previous barrier: write the next tile there, fetch the one after
+        stage((it_tile & 1) ^ 1);       // after the last tile: a tile of clamped rows that nobody reads
+        fetch(key0 + 2 * kPfBKV);
+        // ---- mask, online softmax (per query = per column j: lanes (j, 0) and (j, 1))
+        const bool masked = key0 + kPfBKV - 1 > qmin;  // only tiles that reach past the wave's first query (uniform)
+        float mloc = -INFINITY;
+        if (masked) {
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key0 + 32 * it + 8 * (r >> 2) + 4 * hf + (r & 3);
+                    const float v = (key <= qpos) ? s[it][r] : -INFINITY;
+                    s[it][r] = v;
+                    mloc = fmaxf(mloc, v);
+                }
+        } else {
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+#pragma unroll
+                for (int r = 0; r < 16; r += 4)
+                    mloc = fmaxf(fmaxf(mloc, fmaxf(s[it][r], s[it][r + 1])), fmaxf(s[it][r + 2], s[it][r + 3]));
+        }
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
+        const float mnew = fmaxf(mrun, mloc);
+        // exp2(-inf) = 0 covers the first tile and masked keys; a query with no key yet keeps mnew = -inf
+        const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+        const float corr = __builtin_amdgcn_exp2f((mrun - msafe) * scale2);
+        const float moff = -msafe * scale2;
+        float psum = 0.f;
+        uint4 pk[4];  // B-operand fragments of the four 16-key slabs (it, h2)
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            float p[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                p[r] = __builtin_amdgcn_exp2f(fmaf(s[it][r], scale2, moff));
+                psum += p[r];
+            }
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+                pk[2 * it + h2].x = pack_bf16x2(p[8 * h2 + 0], p[8 * h2 + 1]);
+                pk[2 * it + h2].y = pack_bf16x2(p[8 * h2 + 2], p[8 * h2 + 3]);
+                pk[2 * it + h2].z = pack_bf16x2(p[8 * h2 + 4], p[8 * h2 + 5]);
+                pk[2 * it + h2].w = pack_bf16x2(p[8 * h2 + 6], p[8 * h2 + 7]);
+            }
+        }
+        lrun = lrun * corr + psum;
+        mrun = mnew;
+        if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {  // some query's maximum moved (wave-uniform branch)
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[dt][r] *= corr;
+        }
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) {
+                const uint4 vf = *reinterpret_cast<const uint4*>(Vs + (dt * 4 + sl) * TE + (hf * 32 + j) * 8);
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(attn_bf16x8, vf),
+                                                                  __builtin_bit_cast(attn_bf16x8, pk[sl]), acc[dt], 0, 0, 0);
+            }
+        __syncthreads();  // this stage is free again, the next one is complete
+    }
+
+    // ---- normalise and store: lane (j, hf), registers e, 4 + e, 8 + e, 12 + e hold d = 32 dt + 16 hf + 4 e .. + 3
+    float lt = lrun + __shfl_xor(lrun, 32, kWave);
+    if (tq >= T_new) return;
+    const float inv = 1.0f / lt;
+    bf16_t* out = ctx + ((size_t)l * M + (size_t)b * T_new + tq) * d_model + (size_t)h * DK + 16 * hf;
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint2 o;
+            o.x = pack_bf16x2(acc[dt][e] * inv, acc[dt][4 + e] * inv);
+            o.y = pack_bf16x2(acc[dt][8 + e] * inv, acc[dt][12 + e] * inv);
+            *reinterpret_cast<uint2*>(out + 32 * dt + 4 * e) = o;
+        }
+}
+
 }  // namespace cqil

@@ -183,6 +183,8 @@ def test_set_tuning_error_returns_and_reset():
     assert cq.cqil_workspace_bytes(d, 4, 1, 1) == base
     for bad in (-1, 2):
         assert lib.cqil_set_tuning(b"eq5_fused", bad) == cq.CQIL_EINVAL
+        assert lib.cqil_set_tuning(b"attn_prefill", bad) == cq.CQIL_EINVAL
+    assert lib.cqil_set_tuning(b"attn_prefill", 1) == cq.CQIL_OK and lib.cqil_set_tuning(b"attn_prefill", 0) == cq.CQIL_OK
     assert lib.cqil_set_tuning(b"eq5_fused", 0) == cq.CQIL_OK and lib.cqil_set_tuning(b"eq5_fused", 1) == cq.CQIL_OK
     for bad in (-1, 3):
         assert lib.cqil_set_tuning(b"gemm_tile", bad) == cq.CQIL_EINVAL

@@ -384,10 +384,19 @@ def test_prefill_over_several_query_blocks_and_ragged_caches(shape, dtype):
     QKV product, with both row-to-wave maps (head sizes 128 and 64); ODD keeps the separate pass.  Every position
     is compared."""
     pair = Pair(shape, 2, dtype, max_seq=400, b_max=2, seed=3400, w_std=0.05, gain_jitter=0.1)
-    pair.fill_cache([0, 70], seed=24)
-    pair.step(pair.hidden(2, 300, seed=1), 1, label=f"prefill 2 x 300 {dtype}")
-    pair.set_lens([0, 70])
-    pair.step(pair.hidden(1, 257, seed=2), 0, label=f"prefill 1 x 257 {dtype}")   # one query past two blocks
+    try:
+        for form in ((0, 1) if dtype == torch.bfloat16 else (0,)):     # both matrix-core attention kernels
+            cq.cqil_set_tuning("attn_prefill", form)
+            pair.okc[:] = 0; pair.ovc[:] = 0
+            pair.group.k.zero_(); pair.group.v.zero_()
+            pair.fill_cache([0, 70], seed=24)
+            pair.step(pair.hidden(2, 300, seed=1), 1, label=f"prefill 2 x 300 {dtype} form {form}")
+            pair.set_lens([0, 70])
+            pair.step(pair.hidden(1, 257, seed=2), 0, label=f"prefill 1 x 257 {dtype} form {form}")   # one query past two blocks
+            pair.set_lens([0, 70])
+            pair.step(pair.hidden(2, 64, seed=3), 1, label=f"prefill 2 x 64 {dtype} form {form}")     # half a query block
+    finally:
+        cq.reset_tuning()
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
