@@ -308,6 +308,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma_kernel(
 // Workgroup: 4 waves = 128 queries, key tiles of 64, two LDS stages (16 KiB of K, 16 KiB of V^T each for d_k 128).
 // ---------------------------------------------------------------------------------------------------------
 typedef float attn_f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t attn_u32x2 __attribute__((ext_vector_type(2)));
+constexpr uint32_t kAttnBufFlags = 0x00020000u;  // raw buffer, 32-bit data format (the gfx9 / CDNA encoding)
 
 template <int DK>
 __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma32_kernel(
@@ -369,22 +371,35 @@ __global__ __launch_bounds__(kPfThreads, 2) void attn_prefill_mfma32_kernel(
     uint2 vreg[8];
     const bool v_on = tid < NVG;
     const int v_dq = tid % (DK / 4), v_kgp = (tid / (DK / 4)) & 7;
-    auto fetch = [&](int key0) __attribute__((always_inline)) {
+    // Buffer loads: the descriptor of a tile starts at its first key row and ends at the last valid row, so rows past
+    // the end read as zero without any per-lane clamp (K rows there are masked; V rows must be zero: their
+    // probabilities are zero, but 0 * garbage may be NaN).  Per-lane byte offsets are fixed for the whole kernel.
+    uint32_t k_off[KPT], v_off[8];
 #pragma unroll
-        for (int q = 0; q < KPT; ++q) {
-            const int p = tid + kPfThreads * q;
-            const int slot = min(key0 + p / PPK, kv_end - 1);  // rows past the end: any row, they are masked
-            kreg[q] = *reinterpret_cast<const u32x4*>(kg + (size_t)slot * DK + 8 * (p % PPK));
-        }
+    for (int q = 0; q < KPT; ++q) {
+        const int p = tid + kPfThreads * q;
+        k_off[q] = (uint32_t)(((p / PPK) * DK + 8 * (p % PPK)) * 2);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int key = 16 * (v_kgp >> 1) + 8 * (e >> 2) + 4 * (v_kgp & 1) + (e & 3);
+        v_off[e] = (uint32_t)((key * DK + 4 * v_dq) * 2);
+    }
+    auto fetch = [&](int key0) __attribute__((always_inline)) {
+        const int rows = max(kv_end - key0, 0);            // wave-uniform
+        const uint32_t bytes = (uint32_t)rows * DK * 2;    // at most 64 rows are addressed
+        const __amdgpu_buffer_rsrc_t krs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kg + (size_t)min(key0, kv_end) * DK), 0, bytes, kAttnBufFlags);
+        const __amdgpu_buffer_rsrc_t vrs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vg + (size_t)min(key0, kv_end) * DK), 0, bytes, kAttnBufFlags);
+#pragma unroll
+        for (int q = 0; q < KPT; ++q)
+            kreg[q] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(krs, k_off[q], 0, 0));
         if (v_on) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int key = 16 * (v_kgp >> 1) + 8 * (e >> 2) + 4 * (v_kgp & 1) + (e & 3);
-                const int slot = key0 + key;
-                // V rows past the end must be zero: their probabilities are zero, but 0 * garbage may be NaN
-                const uint2 raw = *reinterpret_cast<const uint2*>(vg + (size_t)min(slot, kv_end - 1) * DK + 4 * v_dq);
-                const uint32_t keep = slot < kv_end ? 0xffffffffu : 0u;
-                vreg[e] = make_uint2(raw.x & keep, raw.y & keep);
+                const attn_u32x2 raw = __builtin_amdgcn_raw_buffer_load_b64(vrs, v_off[e], 0, 0);
+                vreg[e] = make_uint2(raw[0], raw[1]);
             }
         }
     };
