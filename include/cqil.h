@@ -49,7 +49,7 @@ typedef enum { CQIL_F32 = 0, CQIL_BF16 = 1 } cqil_dtype;
 #define CQIL_ATTN_FFN_PARALLEL (-1)
 
 /* Shape of one decoder layer.  Requirements: n_heads * head_dim == d_model; head_dim a power of two,
- * 32..256 (bf16) or 32..128 (fp32); d_model % 32 == 0, at most 14336; d_ffn % 16 == 0; max_seq >= 1. */
+ * 32..256; d_model % 32 == 0, at most 14336; d_ffn % 16 == 0; max_seq >= 1. */
 typedef struct {
     int d_model, n_heads, head_dim, d_ffn, max_seq;
     float rope_base, rms_eps;

@@ -431,6 +431,7 @@ static hipError_t decode_step_t(const StepArgs& s, hipStream_t st) {
         case 8: CQIL_ATTN(8); break;
         case 16: CQIL_ATTN(16); break;
         case 32: CQIL_ATTN(32); break;
+        case 64: CQIL_ATTN(64); break;
         default: return hipErrorInvalidValue;
     }
 #undef CQIL_ATTN

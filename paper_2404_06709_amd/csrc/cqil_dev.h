@@ -68,7 +68,7 @@ __device__ __forceinline__ uint4 load16_stream(const void* p) {
 }
 __device__ __forceinline__ uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 
-// Sum over aligned groups of G consecutive lanes (G = 2 .. 32, a power of two); every lane returns its group's total.
+// Sum over aligned groups of G consecutive lanes (G = 2 .. 64, a power of two); every lane returns its group's total.
 // Up to 16 lanes the partner values come through the ALU's data-parallel lane permutes (within quads: lane ^ 1,
 // lane ^ 2; then the mirror of each half row and of each row of 16), not through the LDS crossbar.
 template <int CTRL>
@@ -82,6 +82,7 @@ __device__ __forceinline__ float lane_group_sum(float v) {
     if (G >= 8) v += dpp_move<0x141>(v);   // row_half_mirror
     if (G >= 16) v += dpp_move<0x140>(v);  // row_mirror
     if (G >= 32) v += __shfl_xor(v, 16, kWave);
+    if (G >= 64) v += __shfl_xor(v, 32, kWave);
     return v;
 }
 

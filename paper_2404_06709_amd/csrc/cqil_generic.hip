@@ -276,7 +276,7 @@ __global__ __launch_bounds__(1024) void bypass_norm_reg_kernel(const T* __restri
                                                               int d_model, float eps, int32_t* __restrict__ kv_len,
                                                               int advance_B, int advance_T) {
     constexpr int V = elem<T>::kVec;
-    __shared__ float scratch[16];
+    __shared__ float scratch[16 * kBypassRegLayers];   // [wave][layer]
     const int m = blockIdx.x, tid = threadIdx.x;
     const bool act = tid < d_model / V;
     const int k = act ? tid * V : 0;
@@ -296,9 +296,12 @@ __global__ __launch_bounds__(1024) void bypass_norm_reg_kernel(const T* __restri
             for (int e = 0; e < V; ++e) av[j][e] = 0.f;
         }
     }
+    // the P sums of squares are reduced together: one pass through LDS (two barriers) for the whole group
+    float ssq[kBypassRegLayers];
 #pragma unroll
     for (int i = 0; i < kBypassRegLayers; ++i) {
-        if (i >= P) break;
+        ssq[i] = 0.f;
+        if (i >= P) continue;
         const int jlo = bypass_d < 0 ? i + 1 : max(0, i - bypass_d);  // negative: Eq.5, the input is x alone
         float hv[V];
 #pragma unroll
@@ -310,13 +313,36 @@ __global__ __launch_bounds__(1024) void bypass_norm_reg_kernel(const T* __restri
                 for (int e = 0; e < V; ++e) hv[e] += av[j][e];
             }
         }
-        float ss = 0.f;
-#pragma unroll
-        for (int e = 0; e < V; ++e) ss += hv[e] * hv[e];
-        ss = block_sum(act ? ss : 0.f, scratch);
-        const float r = 1.0f / sqrtf(ss / (float)d_model + eps);
         if (act) {
-            float gv[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) ssq[i] += hv[e] * hv[e];
+        }
+        ssq[i] = wave_sum(ssq[i]);
+    }
+    const int wv = tid >> 6, nw = blockDim.x >> 6;
+    if ((tid & 63) == 0) {
+#pragma unroll
+        for (int i = 0; i < kBypassRegLayers; ++i) scratch[wv * kBypassRegLayers + i] = ssq[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kBypassRegLayers; ++i) {
+        if (i >= P) break;
+        float tot = 0.f;
+        for (int ww = 0; ww < nw; ++ww) tot += scratch[ww * kBypassRegLayers + i];
+        const float r = 1.0f / sqrtf(tot / (float)d_model + eps);
+        if (act) {
+            const int jlo = bypass_d < 0 ? i + 1 : max(0, i - bypass_d);
+            float hv[V], gv[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) hv[e] = xv[e];
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {
+                if (j >= jlo) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) hv[e] += av[j][e];
+                }
+            }
             elem<T>::unpack(load16(g_ffn + (size_t)i * d_model + k), gv);
 #pragma unroll
             for (int e = 0; e < V; ++e) hv[e] = hv[e] * r * gv[e];
@@ -529,6 +555,7 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
             case 8: CQIL_ATTN1(8); break;
             case 16: CQIL_ATTN1(16); break;
             case 32: CQIL_ATTN1(32); break;
+            case 64: CQIL_ATTN1(64); break;
             default: return hipErrorInvalidValue;
         }
 #undef CQIL_ATTN1
@@ -562,6 +589,7 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
         case 8: CQIL_ATTN(8); break;
         case 16: CQIL_ATTN(16); break;
         case 32: CQIL_ATTN(32); break;
+        case 64: CQIL_ATTN(64); break;
         default: return hipErrorInvalidValue;
     }
 #undef CQIL_ATTN

@@ -20,9 +20,9 @@ int check_dims(const cqil_dims* d, int P) {
     if ((long long)d->n_heads * d->head_dim != d->d_model) return CQIL_EINVAL;
     if (d->d_model % 32 || d->d_ffn % kGuBlock) return CQIL_EINVAL;  // whole tiles of the packed layout
     if (d->d_model > 14336) return CQIL_EINVAL;  // the normalised input of a projection sits in LDS as fp32
-    // lanes sharing one cache slot in the attention kernels: head_dim * esize / 16 must be 4, 8, 16 or 32
+    // lanes sharing one cache slot in the attention kernels: head_dim * esize / 16 must be 4, 8, 16, 32 or 64
     const int lps = d->head_dim * (int)esize(d->dtype) / 16;
-    if (!pow2(d->head_dim) || lps < 4 || lps > 32) return CQIL_EINVAL;
+    if (!pow2(d->head_dim) || lps < 4 || lps > 64) return CQIL_EINVAL;
     if (!(d->rope_base > 1.0f) || !(d->rms_eps >= 0.0f)) return CQIL_EINVAL;
     return CQIL_OK;
 }

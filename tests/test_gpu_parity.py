@@ -235,9 +235,8 @@ def test_every_bypass_distance_decode_and_prefill(P, dtype):
 @pytest.mark.parametrize("head_dim", [32, 256])
 def test_smallest_and_largest_head_sizes(head_dim, dtype):
     """Head sizes at both ends of what the attention kernels take (4 and 32 lanes per cache slot for bf16 heads of
-    32 and 256; 8 lanes for fp32 heads of 32): single-token decode, a batch of decode rows and a short prefill."""
-    if head_dim * (4 if dtype == torch.float32 else 2) // 16 > 32:
-        pytest.skip("fp32 heads of 256 need 64 lanes per slot: rejected by the library (see test_boundary)")
+    32 and 256; 8 and 64 lanes for fp32 heads of 32 and 256): single-token decode, a batch of decode rows and a short
+    prefill."""
     shape = synth.Shape(4 * head_dim, 4, head_dim, 16 * 24)
     pair = Pair(shape, 2, dtype, max_seq=200, b_max=3, seed=2200 + head_dim, w_std=0.05, gain_jitter=0.1)
     pair.fill_cache([150, 0, 37], seed=14)
