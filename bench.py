@@ -34,7 +34,7 @@ MFMA_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
 # what the same counters read for a plain copy kernel (profiles/decode_step_33b_P4_B1_hbm_traffic.md).  Only valid
 # for the workload it was measured on; other workloads report null.
-MEASURED_TRAFFIC = {("33b", 4, "gateup"): 1_909_967_600}
+MEASURED_TRAFFIC = {("33b", 4, "gateup"): 1_909_973_138}
 
 
 def kernel_bytes(shape, P, lens, es=2):
