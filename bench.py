@@ -447,6 +447,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=120)  # about 12 s of oracle work at the 33B shape
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="launch-shape knob of the library (cqil_set_tuning), set before anything is sized or run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -458,6 +460,9 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     cq.lib()  # fails loudly if libcqil.so has not been built
+    for kv in args.tune:
+        key, _, value = kv.partition("=")
+        cq.cqil_set_tuning(key, int(value))
 
     if args.prefill > 0:
         leg = prefill_leg(ctx, args.shape, args.P, args.batch, args.prefill, args.bypass, min(args.steps, 20),

@@ -567,7 +567,7 @@ static hipError_t generic_step_t(const StepArgs& s, hipStream_t st) {
             // 1-D grid: 8 XCDs x groups of kPfUnitGroup head units x query blocks (the kernel skips the padding)
             const int nqb = (s.T + kPfBQ - 1) / kPfBQ, units_per_xcd = (P * s.B * nh + 7) / 8;
             const dim3 grid(8u * ((units_per_xcd + kPfUnitGroup - 1) / kPfUnitGroup) * kPfUnitGroup * nqb);
-            const bool old_form = g_tune.attn_prefill.load() == 1;  // 16x16x32 instructions (half the matrix rate)
+            const bool old_form = g_tune.attn_prefill.load() == 1;  // 16x16x32 instructions (the slower form)
 #define CQIL_PF(KERNEL)                                                                                                  \
     hipLaunchKernelGGL(HIP_KERNEL_NAME(KERNEL), grid, dim3(kPfThreads), 0, st, (const bf16_t*)qkv, (const bf16_t*)s.kc,    \
                        (const bf16_t*)s.vc, s.kv_len, ctx, P, s.B, s.T, nh, d.max_seq, s.b_max)

@@ -4,8 +4,9 @@
 // padded width Kp; a group z (blockIdx.z) addresses a row band (N-concatenation) or a column band
 // (K-concatenation) of it.  C: row-major, bf16 or fp32; fp32 accumulation.
 //
-// Instruction: v_mfma_f32_32x32x16_bf16 (measured on gfx950: it sustains the full matrix rate, the 16x16x32 form
-// half of it).  The weight rows are its A operand (lane i + 32 gg holds row i, columns 8 gg .. 8 gg + 7 of a
+// Instruction: v_mfma_f32_32x32x16_bf16 (measured on gfx950: it sustains the full matrix rate in every arrangement
+// with two waves per SIMD; the 16x16x32 form reaches 45 to 80 % of it, depending on the waves per SIMD and the
+// independent accumulators it is given).  The weight rows are its A operand (lane i + 32 gg holds row i, columns 8 gg .. 8 gg + 7 of a
 // 16-column slab), the tokens its B operand, so a lane ends up with groups of 4 consecutive weight rows of one
 // token: 4 consecutive elements of a C row.
 // A workgroup of WM x WN waves owns 32 TT WM tokens x 64 WN weight rows; a wave owns 32 TT tokens x 64 weight rows
