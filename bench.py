@@ -505,17 +505,19 @@ def main() -> int:
         del leg
         ctx.free()
         cfgs = {}
-        n = min(args.steps, 200)
-        l2 = decode_leg(ctx, "7b", 4, 1, 1024, 0, 128, n, min(args.warmup, 64), 1, seed=1002, cpu_steps=40,
+        # the nested legs keep their own step counts whatever --steps says (each reports them): a short headline
+        # run must not turn them into cold-start measurements
+        n = 200
+        l2 = decode_leg(ctx, "7b", 4, 1, 1024, 0, 128, n, 64, 1, seed=1002, cpu_steps=40,
                         cpu_single_steps=3)
         l2.pop("_group")
         cfgs["llama7b_group_P4_B1_kv1024"] = l2
         ctx.free()
-        lp1 = decode_leg(ctx, "33b", 1, 1, 512, 0, 128, n, min(args.warmup, 64), 0, seed=1005, sequential=False)
+        lp1 = decode_leg(ctx, "33b", 1, 1, 512, 0, 128, n, 64, 0, seed=1005, sequential=False)
         lp1.pop("_group")
         cfgs["llama33b_single_layer_P1_B1_kv512"] = lp1
         ctx.free()
-        l3 = decode_leg(ctx, "13b", 4, 8, 512, 2048, 64, min(n, 128), min(args.warmup, 32), 1, seed=1003,
+        l3 = decode_leg(ctx, "13b", 4, 8, 512, 2048, 64, 128, 32, 1, seed=1003,
                         cpu_steps=3, cpu_single_steps=1)
         l3.pop("_group")
         cfgs["llama13b_group_P4_B8_kv512-2048"] = l3

@@ -356,7 +356,7 @@ int cqil_decode_step_profile(const cqil_dims* dims, int P, int bypass_d, const v
     return rc;
 }
 
-// Model workspace: [x ping][x pong? no: groups run in place][logits][argmax scratch][group workspace]
+// Model workspace: [hidden state (the groups update it in place)][logits][argmax scratch][group workspace]
 static int model_ws(const cqil_model* m, int B, int T, size_t* x_off, size_t* logits_off, size_t* scratch_off,
                     size_t* group_off, size_t* total) {
     if (!m || !m->group_sizes || m->n_groups < 1 || m->vocab < 1 || B < 1 || T < 1) return CQIL_EINVAL;
