@@ -13,7 +13,9 @@ from typing import Dict, List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcqil.so")
+# CQIL_HOST_SANITIZE=1 loads the build whose host code runs under AddressSanitizer + UBSan (see build.py)
+LIB_PATH = os.path.join(_HERE, "libcqil_san.so" if os.environ.get("CQIL_HOST_SANITIZE", "") not in ("", "0")
+                        else "libcqil.so")
 
 CQIL_F32, CQIL_BF16 = 0, 1
 CQIL_ATTN_FFN_PARALLEL = -1   # bypass_d value selecting App. A, Eq.5
